@@ -13,7 +13,7 @@ def test_weights_are_seeded_fp16_with_heavy_tail():
 
 
 def test_a16_outlier_channels():
-    x = goq_inputs.activations_a16(8, 4096, 2, 100, outlier_frac=0.01).astype(np.float64)
+    x = goq_inputs.activations_a16(256, 4096, 2, 100, outlier_frac=0.01).astype(np.float64)
     big = np.flatnonzero(x.std(axis=0) > 8)
     assert len(big) == 41
 
