@@ -1,0 +1,112 @@
+/*
+ * goq.h -- C ABI of the MI355X (gfx950) dual power-of-two linear-layer library.
+ *
+ * What the library computes (GoQuant, "Fully Quantized Inference Dataflow", Eq. 4, read per
+ * 128-wide slab of the input dimension):
+ *
+ *     P_m[t,o,g] = sum_{k in slab g} x[t,k] * b_m[o,k]            m = 1, 2
+ *     y[t,o]     = sum_g ( c1[o,g] * P_1[t,o,g] + c2[o,g] * P_2[t,o,g] )   ( * s_x[t] * 2^-(E-1) for int8 x )
+ *
+ * b_1[o,k] is the power-of-two value of the stored 3- or 4-bit code (asymmetric lattice of
+ * Sec. 3.2: sign + exponent, the smallest positive bin repurposed as exact zero).  b_2 is never
+ * stored: inside every 8-weight micro-block it is rebuilt from b_1 by the Strided Dual-Exchange
+ * of Theorem 1 (partner i xor s, s in 1..4; y_i = -eta x_j, y_j = +eta x_i), configured by the
+ * micro-block's 2-bit pattern index and 4 pair-sign bits (Sec. 3.3 item 3).  c1, c2 are the two
+ * fp16 coefficients of a 128-weight macro-block (Sec. 3.4); they are applied once per slab after
+ * the two dot products, outside the multiply-free core.
+ *
+ * Conventions
+ *   - every function returns GOQ_OK (0) or a negative error; goq_last_error() gives the text of
+ *     the calling thread's last error.  Arguments are validated on the host before any launch.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; no call synchronises, allocates or frees.
+ *   - every pointer named below is a DEVICE pointer unless it says "host".  The caller owns all
+ *     buffers and keeps them alive until the stream has passed the call.  x / X / y / Y and the
+ *     packed buffer must be 16-byte aligned.
+ *   - canonical (logical) weight format, row-major like a linear layer's weight [out][in]:
+ *       codes   u8  [out][in]       code = sign << (bw-1) | e, value (-1)^sign 2^-e,
+ *                                   (sign 0, e = 2^(bw-1)-1) is exact zero
+ *       pattern u8  [out][in/8]     s - 1
+ *       signs   u8  [out][in/8]     bit p = 1  <=>  eta of the p-th pair (ascending i) is -1
+ *       c1, c2  u16 [out][in/128]   IEEE binary16 bit patterns
+ *   - the packed buffer is opaque, position independent (it may be copied or saved) and holds
+ *     exactly 4.0 (bw = 3) or 5.0 (bw = 4) bits per weight, rows padded to a multiple of 64.
+ */
+#ifndef GOQ_H
+#define GOQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    GOQ_OK = 0,
+    GOQ_EINVAL = -1,        /* null / misaligned pointer, bad enum                      */
+    GOQ_ESHAPE = -2,        /* in % 128 != 0, out <= 0, tokens <= 0, too many problems  */
+    GOQ_EUNSUPPORTED = -3,  /* a combination this build does not implement             */
+    GOQ_EHIP = -4           /* a HIP runtime call failed (text in goq_last_error)       */
+};
+
+enum { GOQ_A16 = 0, GOQ_A8 = 1 };   /* activation type: fp16 | int8 (per-token scale)  */
+enum { GOQ_F16 = 0, GOQ_F32 = 1 };  /* output type                                      */
+
+#define GOQ_MAX_BATCH 8             /* problems per goq_gemv_batch call                 */
+
+/* library version, major * 1000 + minor */
+int goq_version(void);
+
+/* text of the calling thread's last error (host pointer, valid until the thread's next call) */
+const char *goq_last_error(void);
+
+/* size in bytes of the packed buffer of a [out][in] layer.  *bytes is a host pointer. */
+int goq_packed_bytes(int bw, int64_t out, int64_t in, size_t *bytes);
+
+/* Stored representation (Sec. 3.3 item 3): canonical arrays -> packed buffer, on the device. */
+int goq_pack(void *stream, int bw, int64_t out, int64_t in,
+             const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs,
+             const uint16_t *c1, const uint16_t *c2, void *packed);
+
+/* Inverse of goq_pack (test hook): packed buffer -> canonical arrays. */
+int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed,
+               uint8_t *codes, uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
+
+/* Batch-1 layer output (Eq. 4 with one token).
+ *   act = GOQ_A16: x is fp16 [in], sx must be NULL.
+ *   act = GOQ_A8 : x is int8 [in], sx points to one fp32 scale (device).
+ *   y is [out] of ytype.  The two slab dot products run on shifts/exponent adds (PoT operands
+ *   decoded to native fp16 / int8), accumulate in fp32 / int32; coefficients are applied per
+ *   slab in fp32.  Results are deterministic for GOQ_F16 output; GOQ_F32 output may use fp32
+ *   atomic accumulation across slabs (summation order not fixed). */
+int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in,
+             const void *packed, const void *x, const float *sx, void *y, int ytype);
+
+/* Several independent batch-1 layers in ONE launch (e.g. the projections of a decoder block).
+ * descs is a HOST array of n <= GOQ_MAX_BATCH descriptors; all must share bw and act. */
+typedef struct goq_gemv_desc {
+    int64_t out, in;
+    const void *packed;
+    const void *x;
+    const float *sx;
+    void *y;
+    int ytype;
+} goq_gemv_desc;
+int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *descs);
+
+/* Many-token layer output (Eq. 4), Y[tokens][out] = X[tokens][in] * W^T.
+ *   act = GOQ_A16: X fp16, sx NULL; PoT codes are decoded to fp16 operands of the fp16 MFMA,
+ *                  fp32 accumulation.
+ *   act = GOQ_A8 : X int8, sx fp32 [tokens]; PoT codes are decoded to int8 (b * 2^(E-1)) operands
+ *                  of the int8 MFMA, exact int32 slab partials.
+ *   partials (optional, GOQ_A8 only, else NULL): int32 [tokens][out][in/128][2] receives the
+ *   exact slab partials P_1, P_2 (in units of 2^-(E-1)). */
+int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t in,
+             const void *packed, const void *X, const float *sx, void *Y, int ytype,
+             int32_t *partials);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GOQ_H */

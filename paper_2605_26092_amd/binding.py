@@ -1,0 +1,117 @@
+"""ctypes binding of include/goq.h: same names, argument marshalling only.
+
+Tensors are torch tensors on the GPU (or anything with .data_ptr()); the current torch stream is
+passed as the hipStream_t.  The library is loaded on first use and a missing build is an error:
+there is no fallback path."""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgoq.so")
+_lib = None
+
+A16, A8 = 0, 1
+F16, F32 = 0, 1
+OK, EINVAL, ESHAPE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+MAX_BATCH = 8
+
+EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_pack", "goq_unpack", "goq_gemv",
+           "goq_gemv_batch", "goq_gemm"]
+
+
+class GoqError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("goq error %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("out", ctypes.c_int64), ("in_", ctypes.c_int64), ("packed", ctypes.c_void_p),
+                ("x", ctypes.c_void_p), ("sx", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("ytype", ctypes.c_int)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libgoq.so is not built: run `python -m paper_2605_26092_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        L.goq_version.restype = i
+        L.goq_last_error.restype = ctypes.c_char_p
+        L.goq_packed_bytes.argtypes = [i, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
+        L.goq_pack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.goq_unpack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.goq_gemv.argtypes = [vp, i, i, i64, i64, vp, vp, vp, vp, i]
+        L.goq_gemv_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc)]
+        L.goq_gemm.argtypes = [vp, i, i, i64, i64, i64, vp, vp, vp, vp, i, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc):
+    if rc != 0:
+        raise GoqError(rc, last_error())
+
+
+def version():
+    return lib().goq_version()
+
+
+def last_error():
+    return lib().goq_last_error().decode()
+
+
+def packed_bytes(bw, out, inn):
+    n = ctypes.c_size_t(0)
+    _check(lib().goq_packed_bytes(bw, out, inn, ctypes.byref(n)))
+    return n.value
+
+
+def pack(bw, out, inn, codes, pattern, signs, c1, c2, packed, stream=None):
+    _check(lib().goq_pack(_stream(stream), bw, out, inn, _ptr(codes), _ptr(pattern), _ptr(signs),
+                          _ptr(c1), _ptr(c2), _ptr(packed)))
+
+
+def unpack(bw, out, inn, packed, codes, pattern, signs, c1, c2, stream=None):
+    _check(lib().goq_unpack(_stream(stream), bw, out, inn, _ptr(packed), _ptr(codes), _ptr(pattern),
+                            _ptr(signs), _ptr(c1), _ptr(c2)))
+
+
+def gemv(bw, act, out, inn, packed, x, sx, y, ytype, stream=None):
+    _check(lib().goq_gemv(_stream(stream), bw, act, out, inn, _ptr(packed), _ptr(x), _ptr(sx), _ptr(y), ytype))
+
+
+def make_descs(problems):
+    """problems: list of (out, in, packed, x, sx, y, ytype) -> ctypes array (host memory)."""
+    arr = (_Desc * len(problems))()
+    for d, (out, inn, packed, x, sx, y, ytype) in zip(arr, problems):
+        d.out, d.in_, d.packed, d.x, d.sx, d.y, d.ytype = out, inn, _ptr(packed), _ptr(x), _ptr(sx), _ptr(y), ytype
+    return arr
+
+
+def gemv_batch(bw, act, problems, stream=None):
+    arr = problems if isinstance(problems, ctypes.Array) else make_descs(problems)
+    _check(lib().goq_gemv_batch(_stream(stream), bw, act, len(arr), arr))
+
+
+def gemm(bw, act, tokens, out, inn, packed, X, sx, Y, ytype, partials=None, stream=None):
+    _check(lib().goq_gemm(_stream(stream), bw, act, tokens, out, inn, _ptr(packed), _ptr(X), _ptr(sx),
+                          _ptr(Y), ytype, _ptr(partials)))

@@ -1,0 +1,128 @@
+// C ABI entry points (include/goq.h): host-side validation, then dispatch to the launchers.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include "goq_internal.h"
+#include "goq_layout.h"
+
+namespace {
+thread_local char g_err[512] = "";
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+}  // namespace
+
+int goq_set_error(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int goq_check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return goq_set_error(GOQ_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return GOQ_OK;
+}
+
+static int check_shape(const char *fn, int bw, int64_t out, int64_t in)
+{
+    if (bw != 3 && bw != 4) return goq_set_error(GOQ_EINVAL, "%s: bw must be 3 or 4 (got %d)", fn, bw);
+    if (out <= 0 || out > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "%s: out = %lld out of range", fn, (long long)out);
+    if (in <= 0 || in % GOQ_N != 0 || in > (1 << 24))
+        return goq_set_error(GOQ_ESHAPE, "%s: in = %lld must be a positive multiple of 128", fn, (long long)in);
+    return GOQ_OK;
+}
+
+extern "C" {
+
+int goq_version(void) { return 1000; }
+
+const char *goq_last_error(void) { return g_err; }
+
+int goq_packed_bytes(int bw, int64_t out, int64_t in, size_t *bytes)
+{
+    if (!bytes) return goq_set_error(GOQ_EINVAL, "goq_packed_bytes: bytes is NULL");
+    int rc = check_shape("goq_packed_bytes", bw, out, in);
+    if (rc) return rc;
+    *bytes = (size_t)goq_packed_dwords(bw, out, in) * 4;
+    return GOQ_OK;
+}
+
+int goq_pack(void *stream, int bw, int64_t out, int64_t in, const uint8_t *codes, const uint8_t *pattern,
+             const uint8_t *signs, const uint16_t *c1, const uint16_t *c2, void *packed)
+{
+    int rc = check_shape("goq_pack", bw, out, in);
+    if (rc) return rc;
+    if (!codes || !pattern || !signs || !c1 || !c2 || !packed)
+        return goq_set_error(GOQ_EINVAL, "goq_pack: NULL pointer");
+    if (misaligned(packed, 16)) return goq_set_error(GOQ_EINVAL, "goq_pack: packed must be 16-byte aligned");
+    return goq_launch_pack((hipStream_t)stream, bw, out, in, codes, pattern, signs, c1, c2, packed);
+}
+
+int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed, uint8_t *codes,
+               uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2)
+{
+    int rc = check_shape("goq_unpack", bw, out, in);
+    if (rc) return rc;
+    if (!codes || !pattern || !signs || !c1 || !c2 || !packed)
+        return goq_set_error(GOQ_EINVAL, "goq_unpack: NULL pointer");
+    if (misaligned(packed, 16)) return goq_set_error(GOQ_EINVAL, "goq_unpack: packed must be 16-byte aligned");
+    return goq_launch_unpack((hipStream_t)stream, bw, out, in, packed, codes, pattern, signs, c1, c2);
+}
+
+static int check_gemv_desc(const char *fn, int bw, int act, const goq_gemv_desc &d)
+{
+    int rc = check_shape(fn, bw, d.out, d.in);
+    if (rc) return rc;
+    if (act != GOQ_A16 && act != GOQ_A8) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
+    if (d.ytype != GOQ_F16 && d.ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "%s: bad output type %d", fn, d.ytype);
+    if (!d.packed || !d.x || !d.y) return goq_set_error(GOQ_EINVAL, "%s: NULL pointer", fn);
+    if (act == GOQ_A8 && !d.sx) return goq_set_error(GOQ_EINVAL, "%s: int8 activations need sx", fn);
+    if (act == GOQ_A16 && d.sx) return goq_set_error(GOQ_EINVAL, "%s: sx must be NULL for fp16 activations", fn);
+    if (misaligned(d.packed, 16) || misaligned(d.x, 16) || misaligned(d.y, 16))
+        return goq_set_error(GOQ_EINVAL, "%s: packed, x and y must be 16-byte aligned", fn);
+    return GOQ_OK;
+}
+
+int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in, const void *packed, const void *x,
+             const float *sx, void *y, int ytype)
+{
+    goq_gemv_desc d;
+    d.out = out; d.in = in; d.packed = packed; d.x = x; d.sx = sx; d.y = y; d.ytype = ytype;
+    int rc = check_gemv_desc("goq_gemv", bw, act, d);
+    if (rc) return rc;
+    return goq_launch_gemv((hipStream_t)stream, bw, act, 1, &d);
+}
+
+int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *descs)
+{
+    if (!descs) return goq_set_error(GOQ_EINVAL, "goq_gemv_batch: descs is NULL");
+    if (n <= 0 || n > GOQ_MAX_BATCH)
+        return goq_set_error(GOQ_ESHAPE, "goq_gemv_batch: n = %d must be in 1..%d", n, GOQ_MAX_BATCH);
+    for (int i = 0; i < n; ++i) {
+        int rc = check_gemv_desc("goq_gemv_batch", bw, act, descs[i]);
+        if (rc) return rc;
+    }
+    return goq_launch_gemv((hipStream_t)stream, bw, act, n, descs);
+}
+
+int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t in, const void *packed,
+             const void *X, const float *sx, void *Y, int ytype, int32_t *partials)
+{
+    int rc = check_shape("goq_gemm", bw, out, in);
+    if (rc) return rc;
+    if (tokens <= 0 || tokens > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "goq_gemm: tokens = %lld out of range", (long long)tokens);
+    if (act != GOQ_A16 && act != GOQ_A8) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad activation type %d", act);
+    if (ytype != GOQ_F16 && ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad output type %d", ytype);
+    if (!packed || !X || !Y) return goq_set_error(GOQ_EINVAL, "goq_gemm: NULL pointer");
+    if (act == GOQ_A8 && !sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: int8 activations need sx");
+    if (act == GOQ_A16 && sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: sx must be NULL for fp16 activations");
+    if (act == GOQ_A16 && partials) return goq_set_error(GOQ_EINVAL, "goq_gemm: partials is only defined for int8 activations");
+    if (misaligned(packed, 16) || misaligned(X, 16) || misaligned(Y, 16))
+        return goq_set_error(GOQ_EINVAL, "goq_gemm: packed, X and Y must be 16-byte aligned");
+    return goq_launch_gemm((hipStream_t)stream, bw, act, tokens, out, in, packed, X, sx, Y, ytype, partials);
+}
+
+}  // extern "C"

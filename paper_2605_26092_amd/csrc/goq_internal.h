@@ -1,0 +1,19 @@
+// Internal (non-ABI) declarations shared by the library's translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/goq.h"
+
+// records the message of a failed launch / HIP call; returns GOQ_OK or GOQ_EHIP
+int goq_check_launch(const char *what);
+int goq_set_error(int code, const char *fmt, ...);
+
+int goq_launch_pack(hipStream_t st, int bw, int64_t out, int64_t in, const uint8_t *codes,
+                    const uint8_t *pattern, const uint8_t *signs, const uint16_t *c1,
+                    const uint16_t *c2, void *packed);
+int goq_launch_unpack(hipStream_t st, int bw, int64_t out, int64_t in, const void *packed,
+                      uint8_t *codes, uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
+int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs);
+int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out, int64_t in,
+                    const void *packed, const void *X, const float *sx, void *Y, int ytype,
+                    int32_t *partials);

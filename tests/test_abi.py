@@ -1,0 +1,61 @@
+"""The C ABI library loads, exports every symbol include/goq.h declares, and rejects bad
+arguments on the host before any launch.  No GPU, no compute calls."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def goq():
+    import paper_2605_26092_amd as g
+    from paper_2605_26092_amd import build
+    build.build(force=False)
+    g.lib()
+    return g
+
+
+def test_every_declared_symbol_is_exported(goq):
+    hdr = open(os.path.join(ROOT, "include", "goq.h")).read()
+    declared = set(re.findall(r"\b(goq_[a-z_0-9]+)\s*\(", hdr))
+    from paper_2605_26092_amd import binding
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(goq.lib(), name), name
+
+
+def test_version_and_packed_bytes(goq):
+    assert goq.version() >= 1000
+    # 4.0 / 5.0 bits per weight, rows padded to 64
+    assert goq.packed_bytes(3, 4096, 4096) == 4096 * 4096 // 2
+    assert goq.packed_bytes(4, 4096, 4096) == 4096 * 4096 * 5 // 8
+    assert goq.packed_bytes(3, 65, 128) == 128 * 128 // 2
+    assert goq.packed_bytes(3, 11008, 4096) == 11008 * 4096 // 2
+
+
+def test_host_side_argument_errors(goq):
+    from paper_2605_26092_amd import binding as b
+    L = goq.lib()
+    n = ctypes.c_size_t()
+    assert L.goq_packed_bytes(5, 64, 128, ctypes.byref(n)) == b.EINVAL
+    assert "bw" in goq.last_error()
+    assert L.goq_packed_bytes(3, 64, 4100, ctypes.byref(n)) == b.ESHAPE
+    assert L.goq_packed_bytes(3, 0, 128, ctypes.byref(n)) == b.ESHAPE
+    assert L.goq_packed_bytes(3, 64, 128, None) == b.EINVAL
+    fake = 0x1000   # never dereferenced: validation fails first
+    assert L.goq_pack(None, 3, 64, 128, None, fake, fake, fake, fake, fake) == b.EINVAL
+    assert L.goq_pack(None, 3, 64, 128, fake, fake, fake, fake, fake, fake + 4) == b.EINVAL
+    assert L.goq_gemv(None, 3, 0, 64, 100, fake, fake, None, fake, 1) == b.ESHAPE
+    assert L.goq_gemv(None, 3, 7, 64, 128, fake, fake, None, fake, 1) == b.EINVAL
+    assert L.goq_gemv(None, 3, 0, 64, 128, fake, fake, None, fake, 9) == b.EINVAL
+    assert L.goq_gemv(None, 3, 1, 64, 128, fake, fake, None, fake, 1) == b.EINVAL      # A8 needs sx
+    assert L.goq_gemv(None, 3, 0, 64, 128, fake, fake, fake, fake, 1) == b.EINVAL      # A16 forbids sx
+    assert L.goq_gemv(None, 3, 0, 64, 128, fake, fake + 2, None, fake, 1) == b.EINVAL  # misaligned x
+    assert L.goq_gemm(None, 3, 0, 0, 64, 128, fake, fake, None, fake, 1, None) == b.ESHAPE
+    assert L.goq_gemm(None, 3, 0, 4, 64, 128, fake, fake, None, fake, 1, fake) == b.EINVAL
+    assert L.goq_gemv_batch(None, 3, 0, 0, None) == b.EINVAL
+    with pytest.raises(goq.GoqError):
+        goq.packed_bytes(3, 64, 64)

@@ -1,0 +1,134 @@
+"""goq_gemv / goq_gemv_batch against the CPU oracle, element by element, on seeded inputs.
+
+Tolerances (A16, fp32 accumulation against the fp64 oracle): max relative error <= 1e-3 with
+the denominator floored at 1 % of the output rms, and normalised backward error
+|y - y^| / sum_k |x_k||W^_ik| <= 1e-3 (expected ~1e-6 for fp32 outputs, ~5e-4 |y| when y is
+stored as fp16).  A8: the slab partials are exact integers by construction; y is held to 1e-5
+normalised error against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import goq_inputs
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+
+
+def _quantize(oracle, bw, out, inn, cid):
+    W = goq_inputs.weights(out, inn, config_id=cid, tensor_id=bw)
+    return oracle.quantize_geo(bw, W, threads=8)
+
+
+def _run_gemv(goq, q, x_np, act, ytype, sx_np=None):
+    torch = gu.torch_cuda()
+    out, inn = q["codes"].shape
+    packed = gu.pack_layer(goq, q)
+    x = gu.to_dev(x_np.reshape(-1))
+    sx = gu.to_dev(sx_np) if sx_np is not None else None
+    y = torch.full((out,), float("nan"), dtype=torch.float32 if ytype == goq.F32 else torch.float16, device="cuda")
+    goq.gemv(q["bw"], act, out, inn, packed, x, sx, y, ytype)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("bw", [3, 4])
+@pytest.mark.parametrize("ytype_name", ["F32", "F16"])
+@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (3, 256), (17, 384), (200, 512), (1100, 1024), (600, 4096)])
+def test_gemv_a16_small(oracle, bw, ytype_name, shape):
+    import paper_2605_26092_amd as goq
+    out, inn = shape
+    print("gemv a16 bw=%d %s out=%d in=%d" % (bw, ytype_name, out, inn), flush=True)
+    q = _quantize(oracle, bw, out, inn, 31)
+    x = goq_inputs.activations_a16(1, inn, config_id=31, tensor_id=100 + out, outlier_frac=0.01)
+    ref = oracle.gemm_a16(q, x, threads=8)[0]
+    y = _run_gemv(goq, q, x, goq.A16, getattr(goq, ytype_name))
+    what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
+    e1, e2 = gu.a16_errors(y, ref, x[0], what_abs)
+    assert e1 <= TOL and e2 <= TOL, (e1, e2)
+    if ytype_name == "F32":
+        assert e2 <= 2e-6, e2
+
+
+@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (17, 384), (200, 768), (1100, 1024)])
+def test_gemv_a8_w3(oracle, shape):
+    import paper_2605_26092_amd as goq
+    out, inn = shape
+    print("gemv a8 out=%d in=%d" % (out, inn), flush=True)
+    q = _quantize(oracle, 3, out, inn, 32)
+    xq, sx = goq_inputs.activations_a8(1, inn, config_id=32, tensor_id=200 + out)
+    ref, _ = oracle.gemm_a8(q, xq, sx, threads=8)
+    y = _run_gemv(goq, q, xq, goq.A8, goq.F32, sx_np=sx)
+    what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
+    scale = (np.abs(xq[0].astype(np.float64)) * float(sx[0])) @ what_abs.T
+    assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5
+
+
+def test_gemv_edge_cases(oracle):
+    """all-zero codes, extreme fp16 activations, int8 saturation, single basis (c2 = 0)."""
+    import paper_2605_26092_amd as goq
+    q = goq_inputs.canonical_random(3, 130, 256, config_id=33)
+    q["codes"][:64] = 3                                   # zero state everywhere in the first 64 rows
+    q["c2"][64:100] = 0                                   # K = 1 rows
+    q["codes"][100:] = 0                                  # all +1
+    x = np.full((1, 256), 65504.0, np.float16)
+    x[0, ::2] = -65504.0
+    x[0, 5] = 6e-8                                        # subnormal
+    ref = oracle.gemm_a16(q, x)[0]
+    y = _run_gemv(goq, q, x, goq.A16, goq.F32)
+    assert np.all(y[:64] == 0.0)
+    what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
+    e1, e2 = gu.a16_errors(y, ref, x[0], what_abs)
+    assert e2 <= 2e-6, e2
+    xq = np.full((1, 256), 127, np.int8)
+    xq[0, 1::2] = -127
+    sx = np.array([0.5], np.float32)
+    ref8, _ = oracle.gemm_a8(q, xq, sx)
+    y8 = _run_gemv(goq, q, xq, goq.A8, goq.F32, sx_np=sx)
+    scale = (np.abs(xq[0].astype(np.float64)) * 0.5) @ what_abs.T
+    assert np.max(np.abs(y8 - ref8[0]) / np.maximum(scale, 1e-30)) <= 1e-5
+    q1 = dict(q)
+    q1["codes"] = np.zeros_like(q["codes"])
+    q1["c1"] = np.full_like(q["c1"], np.float16(1.0).view(np.uint16))
+    q1["c2"] = np.zeros_like(q["c2"])
+    xs = goq_inputs.activations_a16(1, 256, config_id=33)
+    yr = _run_gemv(goq, q1, xs, goq.A16, goq.F32)
+    assert np.allclose(yr, xs.astype(np.float64).sum(), rtol=1e-5)
+
+
+def test_gemv_batch_matches_single_calls(oracle):
+    import paper_2605_26092_amd as goq
+    torch = gu.torch_cuda()
+    shapes = [(256, 512), (1100, 512), (200, 1024)]
+    probs, refs, ys = [], [], []
+    keep = []
+    for i, (out, inn) in enumerate(shapes):
+        q = _quantize(oracle, 3, out, inn, 34 + i)
+        x = goq_inputs.activations_a16(1, inn, config_id=34, tensor_id=i)
+        refs.append(oracle.gemm_a16(q, x, threads=8)[0])
+        packed = gu.pack_layer(goq, q)
+        xd = gu.to_dev(x.reshape(-1))
+        y = torch.full((out,), float("nan"), dtype=torch.float32, device="cuda")
+        keep += [packed, xd]
+        ys.append(y)
+        probs.append((out, inn, packed, xd, None, y, goq.F32))
+    goq.gemv_batch(3, goq.A16, probs)
+    torch.cuda.synchronize()
+    for y, ref in zip(ys, refs):
+        e1, _ = gu.a16_errors(y.cpu().numpy(), ref, None)
+        assert e1 <= TOL, e1
+
+
+@pytest.mark.parametrize("bw", [3, 4])
+def test_gemv_config1_full_size(oracle, bw):
+    """BASELINE config 1: 4096 x 4096, seed 0, batch 1, fp16 N(0,1) activations."""
+    import paper_2605_26092_amd as goq
+    print("gemv config1 bw=%d" % bw, flush=True)
+    q = _quantize(oracle, bw, 4096, 4096, 0)
+    x = goq_inputs.activations_a16(1, 4096, config_id=0, tensor_id=100)
+    ref = oracle.gemm_a16(q, x, threads=8)[0]
+    for ytype in (goq.F32, goq.F16):
+        y = _run_gemv(goq, q, x, goq.A16, ytype)
+        e1, _ = gu.a16_errors(y, ref, None)
+        assert e1 <= TOL, (ytype, e1)
