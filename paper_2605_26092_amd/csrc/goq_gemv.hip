@@ -1,11 +1,18 @@
 // goq_gemv / goq_gemv_batch: batch-1 dual-PoT layer output (Eq. 4 with one token).
 //
-// Work decomposition.  A workgroup of 4 wavefronts takes a ROW GROUP of 4*NRB row blocks
-// (a row block = 64 output channels, one per lane) and a range of macro-blocks g.  For every
-// g the lane that owns row r loads that row's whole macro-block (CH coalesced 16-byte quads,
-// see goq_layout.h) and keeps both slab dot products P1, P2 and the coefficient pair in its own
-// registers, so the slab needs no cross-lane traffic at all; the coefficient rescale (H5) is two
+// Work decomposition.  The unit of work is (row group, macro-block g): a ROW GROUP is 8 row
+// blocks of 64 output channels, one row block per wavefront of a 512-thread workgroup, one row
+// per lane.  The lane that owns row r loads that row's whole macro-block (CH coalesced 16-byte
+// quads, see goq_layout.h) and keeps both slab dot products P1, P2 and the coefficient pair in
+// its own registers, so a slab needs no cross-lane traffic; the coefficient rescale (H5) is two
 // FMAs per 128 weights, after the slab's dot products.
+//
+// All units of all problems of a launch form one linear sequence (problem, row group, g) that
+// is cut into equal contiguous pieces, one per workgroup (two workgroups per CU), so the weight
+// stream of a workgroup is one long prefetched sequence and every workgroup gets the same
+// amount of work whatever the matrix shapes are.  Where a piece ends inside a row group the
+// partial y is combined with fp32 atomic adds (y zeroed by a fill kernel first); when fp16
+// output is requested the pieces are aligned to row groups instead and y is stored directly.
 //
 // Residual basis without rebuilding it: x . b2 = b1 . (T x), where T is the signed exchange
 // of the micro-block (Theorem 1).  T depends only on the micro-block's 6 metadata bits, and
@@ -14,11 +21,9 @@
 // variant its metadata selects with one 16-byte LDS read.  P1 uses x itself, which is uniform
 // across the wavefront (scalar registers).  Per micro-block a lane then spends: 2 byte-LUT
 // permutes (decode), 4 byte shuffles (widen to fp16), 8 two-term fp16 dot products.
-//
-// Output: a workgroup that covers all macro-blocks of its rows stores y directly; otherwise
-// the macro-block ranges are combined with fp32 atomic adds into a y that a fill kernel zeroed.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <type_traits>
 #include "goq_layout.h"
 #include "goq_decode.h"
 #include "goq_internal.h"
@@ -34,19 +39,22 @@ struct GemvProblem {
     int gn;          // macro-blocks per row
     int ytype;
     int rbn;         // row blocks
-    int gper;        // macro-blocks per task
-    int gsplits;     // tasks along g
-    int task_begin;  // first blockIdx of this problem
-    int atomic;      // combine with atomics (y is fp32 and pre-zeroed)
+    int rgroups;     // row groups
+    int begin;       // first piece-space index of this problem (units, or row groups when !split)
 };
 
 struct GemvArgs {
     int n;
+    int split;       // 1: pieces are unit ranges, combine with atomics; 0: pieces are whole row groups
+    int total;       // size of the piece space
     GemvProblem p[GOQ_MAX_BATCH];
 };
 
-constexpr int WAVES = 4;
-constexpr int NRB_DEFAULT = 2;   // row blocks per wavefront
+constexpr int WAVES = 8;   // wavefronts (= row blocks) per workgroup
+
+// x is read-only for the whole kernel: reading it through the constant address space lets the
+// wave-uniform chunk of x live in scalar registers (s_load) instead of 64 identical lanes.
+typedef __attribute__((address_space(4))) uint32_t goq_const_u32;
 
 // Per-thread constants of the exchange variant v = pattern | signs << 2 this thread stages:
 // for output register t (elements 2t, 2t+1): which x register holds the partners, whether the
@@ -105,6 +113,9 @@ template <int BW, int ACT>
 __device__ __forceinline__ uint32_t variant_offset(uint32_t w, const uint4 &meta, int m)
 {
     constexpr int SH = (ACT == 0) ? 4 : 3;
+#ifdef GOQ_EXP_UNIFORM_LDS
+    return 0;
+#endif
     if constexpr (BW == 3) {
         // a_0 (bits 6..7) a_1 (14..15) a_2 (22..23) -> contiguous 6-bit index at bits 18..23
         const uint32_t t = w & 0x00C0C0C0u;
@@ -117,102 +128,274 @@ __device__ __forceinline__ uint32_t variant_offset(uint32_t w, const uint4 &meta
     }
 }
 
-// Stage, for macro-block g, the 64 exchanged copies T x of each of the 16 micro-block positions.
-// Thread (wave, lane) writes variant `lane` of positions wave, wave + 4, ...
+// Staging of the exchanged copies T x of macro-block g, split in two so that the loads of x can
+// be issued a whole slab before they are needed.  Thread (wave, lane) produces variant `lane`
+// of micro-block positions wave and wave + 8.
 template <int ACT>
-__device__ __forceinline__ void stage_table(unsigned char *tb, const void *x, int g, int wave, int lane,
-                                            const Variant &V)
+struct StageRegs {
+    uint32_t v[16 / WAVES][(ACT == 0) ? 4 : 8];
+};
+
+template <int ACT>
+__device__ __forceinline__ void stage_load(StageRegs<ACT> &sr, const void *x, int g, int wave, const Variant &V)
 {
 #pragma unroll
     for (int j = 0; j < 16 / WAVES; ++j) {
         const int m = wave + WAVES * j;
         if constexpr (ACT == 0) {
             const uint32_t *xm = reinterpret_cast<const uint32_t *>(x) + (int64_t)g * 64 + 4 * m;
-            uint4 e;
-            e.x = goq_perm(0u, xm[V.src[0] >> 1], V.swapsel) ^ V.sign[0];
-            e.y = goq_perm(0u, xm[V.src[1] >> 1], V.swapsel) ^ V.sign[1];
-            e.z = goq_perm(0u, xm[V.src[2] >> 1], V.swapsel) ^ V.sign[2];
-            e.w = goq_perm(0u, xm[V.src[3] >> 1], V.swapsel) ^ V.sign[3];
-            *reinterpret_cast<uint4 *>(tb + (m * 64 + lane) * 16) = e;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) sr.v[j][t] = xm[V.src[t] >> 1];
         } else {
             const int8_t *xm = reinterpret_cast<const int8_t *>(x) + (int64_t)g * 128 + 8 * m;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sr.v[j][i] = (uint32_t)(int32_t)xm[V.part[i]];
+        }
+    }
+}
+
+template <int ACT>
+__device__ __forceinline__ void stage_write(unsigned char *tb, const StageRegs<ACT> &sr, int wave, int lane,
+                                            const Variant &V)
+{
+#pragma unroll
+    for (int j = 0; j < 16 / WAVES; ++j) {
+        const int m = wave + WAVES * j;
+        if constexpr (ACT == 0) {
+            uint4 e;
+            e.x = goq_perm(0u, sr.v[j][0], V.swapsel) ^ V.sign[0];
+            e.y = goq_perm(0u, sr.v[j][1], V.swapsel) ^ V.sign[1];
+            e.z = goq_perm(0u, sr.v[j][2], V.swapsel) ^ V.sign[2];
+            e.w = goq_perm(0u, sr.v[j][3], V.swapsel) ^ V.sign[3];
+            *reinterpret_cast<uint4 *>(tb + (m * 64 + lane) * 16) = e;
+        } else {
             uint32_t lo = 0, hi = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                lo |= (uint32_t)(uint8_t)(int8_t)(V.sgn8[i] * xm[V.part[i]]) << (8 * i);
-                hi |= (uint32_t)(uint8_t)(int8_t)(V.sgn8[i + 4] * xm[V.part[i + 4]]) << (8 * i);
+                lo |= (uint32_t)(uint8_t)(int8_t)(V.sgn8[i] * (int32_t)sr.v[j][i]) << (8 * i);
+                hi |= (uint32_t)(uint8_t)(int8_t)(V.sgn8[i + 4] * (int32_t)sr.v[j][i + 4]) << (8 * i);
             }
             *reinterpret_cast<uint2 *>(tb + (m * 64 + lane) * 8) = make_uint2(lo, hi);
         }
     }
 }
 
-// One slab of one row: P1 = x . b1, P2 = (T x) . b1 (H2..H4), then acc += c1 P1 + c2 P2 (H5).
+// Operands of one pipeline stage = one chunk of 4 micro-blocks of one row: the chunk's x
+// (uniform, scalar registers) and the 4 exchanged copies the lane's metadata selects (LDS).
+template <int ACT>
+struct StageOps {
+    uint32_t xs[(ACT == 0) ? 16 : 8];
+    uint4 e[(ACT == 0) ? 4 : 2];
+};
+
+template <int BW, int ACT>
+__device__ __forceinline__ void fetch_stage(StageOps<ACT> &o, const uint4 &d, const uint4 &meta, int h,
+                                            const unsigned char *tb, const void *x, int g)
+{
+    const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
+    if constexpr (ACT == 0) {
+        const goq_const_u32 *xs = reinterpret_cast<const goq_const_u32 *>((uintptr_t)x) + (int64_t)g * 64 + 16 * h;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o.xs[i] = xs[i];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            o.e[q] = *reinterpret_cast<const uint4 *>(tb + (4 * h + q) * 1024 +
+                                                     variant_offset<BW, ACT>(dw[q], meta, 4 * h + q));
+    } else {
+        const goq_const_u32 *xs = reinterpret_cast<const goq_const_u32 *>((uintptr_t)x) + (int64_t)g * 32 + 8 * h;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o.xs[i] = xs[i];
+        uint2 t[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            t[q] = *reinterpret_cast<const uint2 *>(tb + (4 * h + q) * 512 +
+                                                    variant_offset<BW, ACT>(dw[q], meta, 4 * h + q));
+        o.e[0] = make_uint4(t[0].x, t[0].y, t[1].x, t[1].y);
+        o.e[1] = make_uint4(t[2].x, t[2].y, t[3].x, t[3].y);
+    }
+}
+
+// H2..H4 for one chunk: decode, P1 += x . b1, P2 += (T x) . b1; gathers the coefficient bits.
+template <int BW, int ACT, typename AccT>
+__device__ __forceinline__ void compute_stage(const StageOps<ACT> &o, const uint4 &d, AccT &P1, AccT &P2,
+                                              uint32_t &cw)
+{
+    uint32_t dw[4] = {d.x, d.y, d.z, d.w};
+    // pin the chunk's decode to this pipeline stage: without it the compiler hoists the pure
+    // decode arithmetic of all 16 micro-blocks to the top of the slab and runs out of registers
+#pragma unroll
+    for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(dw[q]));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t w = dw[q];
+        uint32_t lo, hi;
+        goq_decode_bytes<BW, ACT>(w, lo, hi);
+        if constexpr (ACT == 0) {
+            const uint32_t b0 = goq_widen01(lo), b1 = goq_widen23(lo);
+            const uint32_t b2 = goq_widen01(hi), b3 = goq_widen23(hi);
+            P1 = goq_dot2(b0, o.xs[4 * q + 0], P1);
+            P1 = goq_dot2(b1, o.xs[4 * q + 1], P1);
+            P1 = goq_dot2(b2, o.xs[4 * q + 2], P1);
+            P1 = goq_dot2(b3, o.xs[4 * q + 3], P1);
+#ifndef GOQ_EXP_NOP2
+            P2 = goq_dot2(b0, o.e[q].x, P2);
+            P2 = goq_dot2(b1, o.e[q].y, P2);
+            P2 = goq_dot2(b2, o.e[q].z, P2);
+            P2 = goq_dot2(b3, o.e[q].w, P2);
+#endif
+        } else {
+            const uint32_t ex = (q & 1) ? o.e[q >> 1].z : o.e[q >> 1].x;
+            const uint32_t ey = (q & 1) ? o.e[q >> 1].w : o.e[q >> 1].y;
+            P1 = goq_dot4(lo, o.xs[2 * q + 0], P1);
+            P1 = goq_dot4(hi, o.xs[2 * q + 1], P1);
+            P2 = goq_dot4(lo, ex, P2);
+            P2 = goq_dot4(hi, ey, P2);
+        }
+        if constexpr (BW == 3) cw = __builtin_amdgcn_alignbit(cw, w, 30);
+    }
+}
+
+// One slab of one row, software pipelined over its 4 chunks: the operands of chunk h+1 are
+// requested (scalar load of x, LDS reads of the exchanged copies) before chunk h is computed.
+// Ends with the coefficient rescale (H5): acc += c1 P1 + c2 P2.
 template <int BW, int ACT>
 __device__ __forceinline__ void slab(const uint4 (&d)[(BW == 3) ? 4 : 5], const unsigned char *tb,
                                      const void *x, int g, float &acc)
 {
+    using AccT = typename std::conditional<ACT == 0, float, int>::type;
     uint32_t cw = 0;
     uint4 meta = make_uint4(0, 0, 0, 0);
     if constexpr (BW == 4) { meta = d[4]; cw = meta.w; }
-    if constexpr (ACT == 0) {
-        const uint32_t *xs = reinterpret_cast<const uint32_t *>(x) + (int64_t)g * 64;
-        float P1 = 0.f, P2 = 0.f;
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const uint32_t dw[4] = {d[h].x, d[h].y, d[h].z, d[h].w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int m = 4 * h + q;
-                const uint32_t w = dw[q];
-                uint32_t lo, hi;
-                goq_decode_bytes<BW, ACT>(w, lo, hi);
-                const uint32_t b0 = goq_widen01(lo), b1 = goq_widen23(lo);
-                const uint32_t b2 = goq_widen01(hi), b3 = goq_widen23(hi);
-                const uint4 e = *reinterpret_cast<const uint4 *>(tb + m * 1024 + variant_offset<BW, ACT>(w, meta, m));
-                P1 = goq_dot2(b0, xs[4 * m + 0], P1);
-                P1 = goq_dot2(b1, xs[4 * m + 1], P1);
-                P1 = goq_dot2(b2, xs[4 * m + 2], P1);
-                P1 = goq_dot2(b3, xs[4 * m + 3], P1);
-                P2 = goq_dot2(b0, e.x, P2);
-                P2 = goq_dot2(b1, e.y, P2);
-                P2 = goq_dot2(b2, e.z, P2);
-                P2 = goq_dot2(b3, e.w, P2);
-                if constexpr (BW == 3) cw = __builtin_amdgcn_alignbit(cw, w, 30);
-            }
-        }
-        const float c1 = __half2float(__ushort_as_half((unsigned short)(cw & 0xffffu)));
-        const float c2 = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
-        acc = fmaf(c1, P1, acc);
-        acc = fmaf(c2, P2, acc);
-    } else {
-        const uint32_t *xs = reinterpret_cast<const uint32_t *>(x) + (int64_t)g * 32;
-        int P1 = 0, P2 = 0;
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const uint32_t dw[4] = {d[h].x, d[h].y, d[h].z, d[h].w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int m = 4 * h + q;
-                const uint32_t w = dw[q];
-                uint32_t lo, hi;
-                goq_decode_bytes<BW, ACT>(w, lo, hi);
-                const uint2 e = *reinterpret_cast<const uint2 *>(tb + m * 512 + variant_offset<BW, ACT>(w, meta, m));
-                P1 = goq_dot4(lo, xs[2 * m + 0], P1);
-                P1 = goq_dot4(hi, xs[2 * m + 1], P1);
-                P2 = goq_dot4(lo, e.x, P2);
-                P2 = goq_dot4(hi, e.y, P2);
-                if constexpr (BW == 3) cw = __builtin_amdgcn_alignbit(cw, w, 30);
-            }
-        }
-        const float c1 = __half2float(__ushort_as_half((unsigned short)(cw & 0xffffu)));
-        const float c2 = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
-        acc = fmaf(c1, (float)P1, acc);
-        acc = fmaf(c2, (float)P2, acc);
-    }
+    AccT P1 = 0, P2 = 0;
+    // Scalar loads return out of order, so any use of one waits for ALL outstanding scalar and
+    // LDS requests.  Each stage therefore first touches its own operands (the wait lands here),
+    // then requests the next stage's, then computes.
+#define GOQ_TOUCH(o) asm volatile("" ::"s"((o).xs[0]), "v"((o).e[0].x))
+    StageOps<ACT> o0, o1;
+    fetch_stage<BW, ACT>(o0, d[0], meta, 0, tb, x, g);
+    GOQ_TOUCH(o0);
+    fetch_stage<BW, ACT>(o1, d[1], meta, 1, tb, x, g);
+    __builtin_amdgcn_sched_barrier(0);
+    compute_stage<BW, ACT>(o0, d[0], P1, P2, cw);
+    __builtin_amdgcn_sched_barrier(0);
+    GOQ_TOUCH(o1);
+    fetch_stage<BW, ACT>(o0, d[2], meta, 2, tb, x, g);
+    __builtin_amdgcn_sched_barrier(0);
+    compute_stage<BW, ACT>(o1, d[1], P1, P2, cw);
+    __builtin_amdgcn_sched_barrier(0);
+    GOQ_TOUCH(o0);
+    fetch_stage<BW, ACT>(o1, d[3], meta, 3, tb, x, g);
+    __builtin_amdgcn_sched_barrier(0);
+    compute_stage<BW, ACT>(o0, d[2], P1, P2, cw);
+    __builtin_amdgcn_sched_barrier(0);
+    GOQ_TOUCH(o1);
+    compute_stage<BW, ACT>(o1, d[3], P1, P2, cw);
+#undef GOQ_TOUCH
+    const float c1 = __half2float(__ushort_as_half((unsigned short)(cw & 0xffffu)));
+    const float c2 = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
+    acc = fmaf(c1, (float)P1, acc);
+    acc = fmaf(c2, (float)P2, acc);
 }
 
-template <int BW, int ACT, int NRB>
+// Position in the linear unit sequence.
+struct Cursor {
+    int pi, rg, g;
+};
+
+__device__ __forceinline__ Cursor locate(const GemvArgs &a, int idx)
+{
+    Cursor c;
+    if (idx >= a.total) { c.pi = a.n; c.rg = 0; c.g = 0; return c; }
+    int pi = 0;
+    while (pi + 1 < a.n && idx >= a.p[pi + 1].begin) ++pi;
+    const int local = idx - a.p[pi].begin;
+    c.pi = pi;
+    if (a.split) { c.rg = local / a.p[pi].gn; c.g = local % a.p[pi].gn; }
+    else { c.rg = local; c.g = 0; }
+    return c;
+}
+
+__device__ __forceinline__ bool same(const Cursor &a, const Cursor &b)
+{
+    return a.pi == b.pi && a.rg == b.rg && a.g == b.g;
+}
+
+// The few fields of a problem the streaming loop needs (kept in scalar registers); the output
+// side (y, out, sx, ytype) is re-read from the kernel arguments only when a row group is flushed.
+struct Stream {
+    const uint32_t *packed;
+    const void *x;
+    int gn, rbn, rgroups;
+};
+
+__device__ __forceinline__ Stream stream_of(const GemvArgs &a, int pi)
+{
+    Stream s;
+    s.packed = a.p[pi].packed;
+    s.x = a.p[pi].x;
+    s.gn = a.p[pi].gn;
+    s.rbn = a.p[pi].rbn;
+    s.rgroups = a.p[pi].rgroups;
+    return s;
+}
+
+// One unit: prefetch the next unit's weights and x, compute this unit's slab, publish the next
+// unit's table.  Invariant on entry: tcur holds this unit's exchanged copies and every wave has
+// passed the barrier after they were written.  Returns false after the piece's last unit.
+template <int BW, int ACT>
+__device__ __forceinline__ bool gemv_unit(const GemvArgs &a, Cursor &cur, const Cursor &end, Stream &S,
+                                          uint4 (&bcur)[(BW == 3) ? 4 : 5], uint4 (&bnxt)[(BW == 3) ? 4 : 5],
+                                          unsigned char *tcur, unsigned char *tnxt, StageRegs<ACT> &sr,
+                                          const Variant &V, float &acc, int wave, int lane)
+{
+    Cursor nxt = cur;
+    if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
+    const bool more = !same(nxt, end);
+    const bool new_problem = more && nxt.pi != cur.pi;
+    Stream Sn = S;
+    if (new_problem) Sn = stream_of(a, nxt.pi);
+    if (more) {
+        const int Rn = nxt.rg * WAVES + wave;
+#ifndef GOQ_EXP_NOMEM
+        if (Rn < Sn.rbn) load_block<BW>(Sn.packed, Sn.gn, Rn, nxt.g, lane, bnxt);
+#endif
+        stage_load<ACT>(sr, Sn.x, nxt.g, wave, V);
+    }
+    const int R = cur.rg * WAVES + wave;
+#ifdef GOQ_EXP_READONLY
+    if (R < S.rbn) {
+        uint32_t t = 0;
+        for (int h = 0; h < ((BW == 3) ? 4 : 5); ++h) t ^= bcur[h].x ^ bcur[h].y ^ bcur[h].z ^ bcur[h].w;
+        acc += (float)t;
+    }
+#else
+    if (R < S.rbn) slab<BW, ACT>(bcur, tcur, S.x, cur.g, acc);
+#endif
+    if (!more || nxt.rg != cur.rg || new_problem) {
+        // ---- reduce + store (H6): the lane owns the row, nothing to reduce inside the wave
+        const GemvProblem &P = a.p[cur.pi];
+        float v = acc;
+        if constexpr (ACT == 1) v *= P.sx[0] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
+        const int row = R * GOQ_ROWS + lane;
+        if (R < S.rbn && row < P.out) {
+            if (a.split) atomicAdd(reinterpret_cast<float *>(P.y) + row, v);
+            else if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row] = v;
+            else reinterpret_cast<__half *>(P.y)[row] = __float2half(v);
+        }
+        acc = 0.f;
+    }
+    if (more) {
+        stage_write<ACT>(tnxt, sr, wave, lane, V);
+#ifndef GOQ_EXP_NOBARRIER
+        __syncthreads();
+#endif
+    }
+    cur = nxt;
+    S = Sn;
+    return more;
+}
+
+template <int BW, int ACT>
 __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvArgs a)
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
@@ -223,86 +406,51 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    int pi = 0;
-    while (pi + 1 < a.n && (int)blockIdx.x >= a.p[pi + 1].task_begin) ++pi;
-    const GemvProblem P = a.p[pi];
-    const int task = blockIdx.x - P.task_begin;
-    const int gs = task % P.gsplits;
-    const int rg = task / P.gsplits;
-    const int g0 = gs * P.gper;
-    const int g1 = min(g0 + P.gper, P.gn);
-    const int Rbase = (rg * WAVES + wave) * NRB;
-    const int64_t gn = P.gn;
+    // this workgroup's piece [i0, i1) of the piece space
+    const int64_t nwg = gridDim.x;
+    const int i0 = (int)((int64_t)a.total * blockIdx.x / nwg);
+    const int i1 = (int)((int64_t)a.total * (blockIdx.x + 1) / nwg);
+    if (i0 >= i1) return;
+    Cursor cur = locate(a, i0);
+    const Cursor end = locate(a, i1);
+    Stream S = stream_of(a, cur.pi);
 
     const Variant V = make_variant(lane);
+    float acc = 0.f;
+    uint4 bufA[CH], bufB[CH];
+#ifdef GOQ_EXP_NOMEM
+    for (int h = 0; h < CH; ++h)
+        bufA[h] = bufB[h] = make_uint4(lane * 0x01234567u, lane * 0x89abcdefu + h, lane ^ 0x5a5a5a5au, h * 0x11111111u);
+#endif
+    StageRegs<ACT> sr;
 
-    float acc[NRB];
-#pragma unroll
-    for (int i = 0; i < NRB; ++i) acc[i] = 0.f;
-
-    // two register buffers per row block: one being consumed, one being filled from HBM
-    uint4 bufA[NRB][CH], bufB[NRB][CH];
-#pragma unroll
-    for (int i = 0; i < NRB; ++i)
-        if (Rbase + i < P.rbn) load_block<BW>(P.packed, gn, Rbase + i, g0, lane, bufA[i]);
-
-    for (int g = g0; g < g1; g += 2) {
-        stage_table<ACT>(table[0], P.x, g, wave, lane, V);
-        if (g + 1 < g1) {
-#pragma unroll
-            for (int i = 0; i < NRB; ++i)
-                if (Rbase + i < P.rbn) load_block<BW>(P.packed, gn, Rbase + i, g + 1, lane, bufB[i]);
-        }
+    {
+        const int R = cur.rg * WAVES + wave;
+#ifndef GOQ_EXP_NOMEM
+        if (R < S.rbn) load_block<BW>(S.packed, S.gn, R, cur.g, lane, bufA);
+#endif
+        stage_load<ACT>(sr, S.x, cur.g, wave, V);
+        stage_write<ACT>(table[0], sr, wave, lane, V);
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NRB; ++i)
-            if (Rbase + i < P.rbn) slab<BW, ACT>(bufA[i], table[0], P.x, g, acc[i]);
-        if (g + 1 < g1) {
-            stage_table<ACT>(table[1], P.x, g + 1, wave, lane, V);
-            if (g + 2 < g1) {
-#pragma unroll
-                for (int i = 0; i < NRB; ++i)
-                    if (Rbase + i < P.rbn) load_block<BW>(P.packed, gn, Rbase + i, g + 2, lane, bufA[i]);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < NRB; ++i)
-                if (Rbase + i < P.rbn) slab<BW, ACT>(bufB[i], table[1], P.x, g + 1, acc[i]);
-        }
     }
-
-    // ---- reduce + store (H6): the lane owns the row, nothing to reduce inside the wave
-    float post = 1.f;
-    if constexpr (ACT == 1) post = P.sx[0] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
-#pragma unroll
-    for (int i = 0; i < NRB; ++i) {
-        const int row = (Rbase + i) * GOQ_ROWS + lane;
-        if (Rbase + i >= P.rbn || row >= P.out) continue;
-        const float v = acc[i] * post;
-        if (P.atomic) {
-            atomicAdd(reinterpret_cast<float *>(P.y) + row, v);
-        } else if (P.ytype == GOQ_F32) {
-            reinterpret_cast<float *>(P.y)[row] = v;
-        } else {
-            reinterpret_cast<__half *>(P.y)[row] = __float2half(v);
-        }
+    while (true) {
+        if (!gemv_unit<BW, ACT>(a, cur, end, S, bufA, bufB, table[0], table[1], sr, V, acc, wave, lane)) break;
+        if (!gemv_unit<BW, ACT>(a, cur, end, S, bufB, bufA, table[1], table[0], sr, V, acc, wave, lane)) break;
     }
 }
 
 __global__ __launch_bounds__(256) void zero_kernel(GemvArgs a)
 {
     const GemvProblem &P = a.p[blockIdx.y];
-    if (!P.atomic) return;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < P.out; i += gridDim.x * blockDim.x)
         reinterpret_cast<float *>(P.y)[i] = 0.f;
 }
 
 template <int BW, int ACT>
-int launch(hipStream_t st, const GemvArgs &a, int total, bool any_atomic)
+int launch(hipStream_t st, const GemvArgs &a, int nwg)
 {
-    constexpr int NRB = NRB_DEFAULT;
-    if (any_atomic) hipLaunchKernelGGL(zero_kernel, dim3(16, a.n), dim3(256), 0, st, a);
-    hipLaunchKernelGGL((gemv_kernel<BW, ACT, NRB>), dim3(total), dim3(WAVES * 64), 0, st, a);
+    if (a.split) hipLaunchKernelGGL(zero_kernel, dim3(8, a.n), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((gemv_kernel<BW, ACT>), dim3(nwg), dim3(WAVES * 64), 0, st, a);
     return goq_check_launch("goq_gemv");
 }
 
@@ -310,15 +458,12 @@ int launch(hipStream_t st, const GemvArgs &a, int total, bool any_atomic)
 
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs)
 {
-    constexpr int NRB = NRB_DEFAULT;
     GemvArgs a;
     a.n = n;
-    int total = 0;
-    bool any_atomic = false;
-    // how finely to split the macro-block range: enough workgroups to fill 256 CUs a few times
-    int64_t rowgroups_total = 0;
+    a.split = 1;
     for (int i = 0; i < n; ++i)
-        rowgroups_total += (goq_row_blocks(descs[i].out) + WAVES * NRB - 1) / (WAVES * NRB);
+        if (descs[i].ytype != GOQ_F32) a.split = 0;     // fp16 y cannot take atomic partial sums
+    int total = 0;
     for (int i = 0; i < n; ++i) {
         GemvProblem &P = a.p[i];
         P.packed = (const uint32_t *)descs[i].packed;
@@ -329,24 +474,20 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
         P.gn = (int)(descs[i].in / GOQ_N);
         P.ytype = descs[i].ytype;
         P.rbn = (int)goq_row_blocks(descs[i].out);
-        const int rgroups = (P.rbn + WAVES * NRB - 1) / (WAVES * NRB);
-        int gper = P.gn;
-        if (descs[i].ytype == GOQ_F32) {
-            // aim at >= 1024 workgroups per launch, at least 2 macro-blocks per task
-            const int64_t want_splits = (1024 + rowgroups_total - 1) / rowgroups_total;
-            gper = (int)((P.gn + want_splits - 1) / want_splits);
-            if (gper < 2) gper = P.gn < 2 ? P.gn : 2;
-        }
-        P.gper = gper;
-        P.gsplits = (P.gn + gper - 1) / gper;
-        P.atomic = P.gsplits > 1 ? 1 : 0;
-        any_atomic |= P.atomic != 0;
-        P.task_begin = total;
-        total += rgroups * P.gsplits;
+        P.rgroups = (P.rbn + WAVES - 1) / WAVES;
+        P.begin = total;
+        total += a.split ? P.rgroups * P.gn : P.rgroups;
     }
-    for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].task_begin = 0x7fffffff; }
-    if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, total, any_atomic);
-    if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a, total, any_atomic);
-    if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, a, total, any_atomic);
+    for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].begin = 0x7fffffff; }
+    a.total = total;
+    // two 512-thread workgroups per CU fill the register file (4 wavefronts per SIMD)
+    int nwg = 2 * 256;
+#ifdef GOQ_EXP_NWG
+    nwg = GOQ_EXP_NWG;
+#endif
+    if (nwg > total) nwg = total;
+    if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, nwg);
+    if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a, nwg);
+    if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, a, nwg);
     return goq_set_error(GOQ_EUNSUPPORTED, "goq_gemv: bw=4 with int8 activations is not implemented");
 }
