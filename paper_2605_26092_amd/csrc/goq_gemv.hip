@@ -312,6 +312,10 @@ __device__ __forceinline__ Cursor locate(const GemvArgs &a, int idx)
     c.pi = pi;
     if (a.split) { c.rg = local / a.p[pi].gn; c.g = local % a.p[pi].gn; }
     else { c.rg = local; c.g = 0; }
+    // the divisions run on the vector ALU: move the (uniform) results back to scalar registers
+    // so that all later cursor and address arithmetic is scalar
+    c.rg = __builtin_amdgcn_readfirstlane(c.rg);
+    c.g = __builtin_amdgcn_readfirstlane(c.g);
     return c;
 }
 
@@ -408,8 +412,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvArgs a)
 
     // this workgroup's piece [i0, i1) of the piece space
     const int64_t nwg = gridDim.x;
-    const int i0 = (int)((int64_t)a.total * blockIdx.x / nwg);
-    const int i1 = (int)((int64_t)a.total * (blockIdx.x + 1) / nwg);
+    const int i0 = __builtin_amdgcn_readfirstlane((int)((int64_t)a.total * blockIdx.x / nwg));
+    const int i1 = __builtin_amdgcn_readfirstlane((int)((int64_t)a.total * (blockIdx.x + 1) / nwg));
     if (i0 >= i1) return;
     Cursor cur = locate(a, i0);
     const Cursor end = locate(a, i1);
