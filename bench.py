@@ -117,8 +117,52 @@ def bench_gemv(args, shapes, bw, name):
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "gemv_kernel<3,0,2>", "avg_launch_us": round(dev_ms * 1e3, 3)},
     }
+    if args.gemm_tokens > 0:
+        res["gemm"] = bench_gemm_block(args, shapes, bw, goq.A16, packed0, args.gemm_tokens)
     res["cpu_baseline"] = cpu_baseline_gemv(canon, shapes, bw, alg_bytes) if not args.no_cpu else None
     return res
+
+
+def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
+    """The same block as many-token GEMMs (one launch per matrix): issued ops = 4 M N K (two PoT
+    bases), dense-equivalent = 2 M N K.  Reported next to the headline, not instead of it."""
+    import torch
+    import paper_2605_26092_amd as goq
+    dev = torch.device("cuda:0")
+    Xs, Ys, sxs = [], [], []
+    for idx, (_, out, inn) in enumerate(shapes):
+        if act == goq.A16:
+            x = goq_inputs.activations_a16(tokens, inn, config_id=3, tensor_id=100 + idx, outlier_frac=0.01)
+            sxs.append(None)
+        else:
+            x, sx = goq_inputs.activations_a8(tokens, inn, config_id=4, tensor_id=200 + idx)
+            sxs.append(torch.from_numpy(sx).to(dev))
+        Xs.append(torch.from_numpy(x).to(dev))
+        Ys.append(torch.zeros((tokens, out), dtype=torch.float16, device=dev))
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for k, (_, out, inn) in enumerate(shapes):
+            goq.gemm(bw, act, tokens, out, inn, packed[k], Xs[k], sxs[k], Ys[k], goq.F16, stream=stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    issued = 4.0 * tokens * sum(o * i for _, o, i in shapes)
+    peak = MFMA_F16_PEAK_TFLOPS if act == goq.A16 else MFMA_I8_PEAK_TOPS
+    tops = issued / (ms * 1e-3) / 1e12
+    return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, "A16" if act == goq.A16 else "A8"),
+            "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1), "dense_equiv_TOPS": round(tops / 2, 1),
+            "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if act == goq.A16 else "TOP/s",
+                         "frac": round(tops / peak, 4), "traffic": None}}
 
 
 def cpu_baseline_gemv(canon, shapes, bw, alg_bytes):
@@ -146,6 +190,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--gemm-tokens", type=int, default=2048,
+                    help="also time the block as GEMMs with this many tokens (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives are part of the path); "
