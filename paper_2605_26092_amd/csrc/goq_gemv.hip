@@ -335,11 +335,14 @@ struct Stream {
 __device__ __forceinline__ Stream stream_of(const GemvArgs &a, int pi)
 {
     Stream s;
-    s.packed = a.p[pi].packed;
-    s.x = a.p[pi].x;
-    s.gn = a.p[pi].gn;
-    s.rbn = a.p[pi].rbn;
-    s.rgroups = a.p[pi].rgroups;
+    const uint64_t pk = (uint64_t)a.p[pi].packed, px = (uint64_t)a.p[pi].x;
+    s.packed = (const uint32_t *)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(pk >> 32)) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)pk));
+    s.x = (const void *)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(px >> 32)) << 32) |
+                         (uint32_t)__builtin_amdgcn_readfirstlane((int)px));
+    s.gn = __builtin_amdgcn_readfirstlane(a.p[pi].gn);
+    s.rbn = __builtin_amdgcn_readfirstlane(a.p[pi].rbn);
+    s.rgroups = __builtin_amdgcn_readfirstlane(a.p[pi].rgroups);
     return s;
 }
 
@@ -354,6 +357,10 @@ __device__ __forceinline__ bool gemv_unit(const GemvArgs &a, Cursor &cur, const 
 {
     Cursor nxt = cur;
     if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
+    // the cursor is wave-uniform: keep it (and everything derived from it) in scalar registers
+    nxt.pi = __builtin_amdgcn_readfirstlane(nxt.pi);
+    nxt.rg = __builtin_amdgcn_readfirstlane(nxt.rg);
+    nxt.g = __builtin_amdgcn_readfirstlane(nxt.g);
     const bool more = !same(nxt, end);
     const bool new_problem = more && nxt.pi != cur.pi;
     Stream Sn = S;
