@@ -50,7 +50,10 @@ struct GemvArgs {
     GemvProblem p[GOQ_MAX_BATCH];
 };
 
-constexpr int WAVES = 8;   // wavefronts (= row blocks) per workgroup
+#ifndef GOQ_EXP_WAVES
+#define GOQ_EXP_WAVES 8
+#endif
+constexpr int WAVES = GOQ_EXP_WAVES;   // wavefronts (= row blocks) per workgroup
 
 // x is read-only for the whole kernel: reading it through the constant address space lets the
 // wave-uniform chunk of x live in scalar registers (s_load) instead of 64 identical lanes.
@@ -102,7 +105,11 @@ __device__ __forceinline__ void load_block(const uint32_t *__restrict__ packed, 
     const u32x4 *base = reinterpret_cast<const u32x4 *>(packed + goq_quad_index(CH, gn, R, g, 0, lane));
 #pragma unroll
     for (int h = 0; h < CH; ++h) {
+#ifdef GOQ_EXP_NONT
+        const u32x4 v = base[h * GOQ_ROWS];
+#else
         const u32x4 v = __builtin_nontemporal_load(base + h * GOQ_ROWS);   // streamed once: no reuse
+#endif
         d[h] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
@@ -217,14 +224,14 @@ __device__ __forceinline__ void fetch_stage(StageOps<ACT> &o, const uint4 &d, co
 
 // H2..H4 for one chunk: decode, P1 += x . b1, P2 += (T x) . b1; gathers the coefficient bits.
 template <int BW, int ACT, typename AccT>
-__device__ __forceinline__ void compute_stage(const StageOps<ACT> &o, const uint4 &d, AccT &P1, AccT &P2,
+__device__ __forceinline__ void compute_stage(const StageOps<ACT> &o, uint4 &d, AccT &P1, AccT &P2,
                                               uint32_t &cw)
 {
-    uint32_t dw[4] = {d.x, d.y, d.z, d.w};
-    // pin the chunk's decode to this pipeline stage: without it the compiler hoists the pure
-    // decode arithmetic of all 16 micro-blocks to the top of the slab and runs out of registers
-#pragma unroll
-    for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(dw[q]));
+    // pin the chunk's decode to this pipeline stage (in place, no copies): without it the compiler
+    // hoists the pure decode arithmetic of all 16 micro-blocks to the top of the slab and runs out
+    // of registers
+    asm volatile("" : "+v"(d.x), "+v"(d.y), "+v"(d.z), "+v"(d.w));
+    const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const uint32_t w = dw[q];
@@ -259,7 +266,7 @@ __device__ __forceinline__ void compute_stage(const StageOps<ACT> &o, const uint
 // requested (scalar load of x, LDS reads of the exchanged copies) before chunk h is computed.
 // Ends with the coefficient rescale (H5): acc += c1 P1 + c2 P2.
 template <int BW, int ACT>
-__device__ __forceinline__ void slab(const uint4 (&d)[(BW == 3) ? 4 : 5], const unsigned char *tb,
+__device__ __forceinline__ void slab(uint4 (&d)[(BW == 3) ? 4 : 5], const unsigned char *tb,
                                      const void *x, int g, float &acc)
 {
     using AccT = typename std::conditional<ACT == 0, float, int>::type;
