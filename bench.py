@@ -115,8 +115,23 @@ def bench_gemv(args, shapes, bw, name):
                    "cache_resident_GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "gemv_kernel<3,0,2>", "avg_launch_us": round(dev_ms * 1e3, 3)},
+                     "kernel": "gemv_kernel<%d,0>" % bw, "avg_launch_us": round(dev_ms * 1e3, 3)},
     }
+    # HBM traffic per launch from the committed counter runs (FETCH_SIZE + WRITE_SIZE, scaled), if present
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json.txt")) as fh:
+            res["roofline"]["traffic"] = json.load(fh)["gemv_kernel<3,0>"]["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        pass
+    if args.traffic_ref:
+        # reference dispatches of known traffic for scaling FETCH_SIZE / WRITE_SIZE counter runs:
+        # an elementwise add over 64 Mi int32 reads 256 MiB and writes 256 MiB
+        src = torch.ones(64 << 20, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     if args.gemm_tokens > 0:
         res["gemm"] = bench_gemm_block(args, shapes, bw, goq.A16, packed0, args.gemm_tokens)
     res["cpu_baseline"] = cpu_baseline_gemv(canon, shapes, bw, alg_bytes) if not args.no_cpu else None
@@ -190,6 +205,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--traffic-ref", action="store_true",
+                    help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
     ap.add_argument("--gemm-tokens", type=int, default=2048,
                     help="also time the block as GEMMs with this many tokens (0 = skip)")
     args = ap.parse_args()
