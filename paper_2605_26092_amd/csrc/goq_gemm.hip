@@ -10,13 +10,15 @@
 // micro-block in registers with the byte LUT (H2), and rebuilds the residual basis b2 of the same
 // micro-block in registers too (H4): a byte permute by i xor s plus sign flips, both looked up by
 // the 6 metadata bits in a 1 KiB LDS table built at kernel start.  No decoded weight ever goes
-// through memory.  The activation tile of the current 128-wide slab is staged in LDS (row stride
-// padded by 16 B against bank conflicts) and read as the MFMA A operand.
+// through memory.  The activation tile of the current 128-wide slab is staged in LDS (XOR-swizzled
+// 16-byte pieces against bank conflicts) and read as the MFMA A operand.
 //
-// Tiling: workgroup = 4 wavefronts, tile 128 tokens x 128 outputs; each wavefront owns
-// 128 tokens x 32 outputs = 8 x 2 MFMA tiles, with three accumulator sets: the slab partials
-// P1, P2 (restarted every slab by feeding C = 0 to the slab's first MFMA; only one tile column
-// of them is live at a time) and the output Y.
+// Tiling: workgroup = 4 wavefronts, tile 64 tokens x 128 outputs; each wavefront owns
+// 64 tokens x 32 outputs = 4 x 2 MFMA tiles, with three accumulator sets: the slab partials
+// P1, P2 (restarted every slab by feeding C = 0 to the slab's first MFMA) and the output Y.
+// That fits two wavefronts per SIMD, which measured faster than a 128-token tile at one.
+// The next slab's weights (registers) and activations (global_load_lds straight into the other
+// LDS buffer) are requested before the current slab's MFMAs; one barrier per slab.
 // Coefficient rescale (H5) once per slab: Y += c1[n,g] * P1 + c2[n,g] * P2 in fp32, after the
 // slab's MFMAs; a lane needs one (c1, c2) pair per MFMA tile column because every accumulator
 // register of a lane belongs to the same output channel.
@@ -33,7 +35,10 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TM = 128;       // tokens per workgroup tile
+#ifndef GOQ_GEMM_TM
+#define GOQ_GEMM_TM 64
+#endif
+constexpr int TM = GOQ_GEMM_TM;   // tokens per workgroup tile
 constexpr int TN = 128;       // outputs per workgroup tile
 constexpr int WN = 32;        // outputs per wavefront
 constexpr int MS = TM / 16;   // MFMA tiles along tokens per wavefront
@@ -121,15 +126,19 @@ __device__ __forceinline__ f16x8 widen8(uint32_t lo, uint32_t hi)
 }
 
 template <int BW, int ACT, bool PART>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs a)
+#ifndef GOQ_GEMM_MINWAVES
+#define GOQ_GEMM_MINWAVES 2
+#endif
+__global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a)
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
     constexpr int XB = (ACT == 0) ? 2 : 1;             // bytes per activation
-    constexpr int ROWB = GOQ_N * XB + 16;              // padded LDS row stride
+    constexpr int ROWB = GOQ_N * XB;                   // LDS row stride (XOR-swizzled, not padded)
     constexpr int KSTEPS = (ACT == 0) ? 4 : 2;         // MFMA k-steps per slab
     using AccT = typename std::conditional<ACT == 0, f32x4, i32x4>::type;
 
-    __shared__ __attribute__((aligned(16))) unsigned char xs[TM * ROWB];
+    __shared__ __attribute__((aligned(16))) unsigned char xs0[TM * ROWB];
+    __shared__ __attribute__((aligned(16))) unsigned char xs1[TM * ROWB];
     __shared__ __attribute__((aligned(16))) unsigned char xtab[64 * 16];
 
     const int tid = threadIdx.x;
@@ -163,9 +172,12 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs a)
     }
     const int64_t gstride = (int64_t)CH * GOQ_ROWS * 4;     // dwords between macro-blocks
 
-    for (int g = 0; g < a.gn; ++g) {
-        // ---- weights of this slab: one quad (+ the metadata quad for bw = 4) per column tile
-        uint4 wd[NS], meta[NS];
+    // 16-byte pieces of the activation slab this thread moves from HBM to LDS
+    constexpr int PIECES = TM * GOQ_N * XB / 16;
+    constexpr int PER_ROW = GOQ_N * XB / 16;
+    constexpr int NP = PIECES / 256;
+    auto swz = [](int row) { return (ACT == 0) ? (row & 15) : ((row >> 1) & 7); };
+    auto load_weights = [&](int g, uint4 (&wd)[NS], uint4 (&meta)[NS]) {
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
             wd[j] = make_uint4(0, 0, 0, 0);
@@ -179,22 +191,47 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs a)
                 }
             }
         }
-        // ---- stage the activation slab X[m0 .. m0+127][128 g .. 128 g + 127] in LDS
-        __syncthreads();      // previous slab's readers are done
-        {
-            constexpr int PIECES = TM * GOQ_N * XB / 16;        // 16-byte pieces in the tile
-            constexpr int PER_ROW = GOQ_N * XB / 16;
-#pragma unroll 2
-            for (int p = tid; p < PIECES; p += 256) {
-                const int row = p / PER_ROW, c = p % PER_ROW;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (m0 + row < a.tokens)
-                    v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.X) +
-                                                         ((int64_t)(m0 + row) * a.in + (int64_t)g * GOQ_N) * XB + c * 16);
-                *reinterpret_cast<uint4 *>(xs + row * ROWB + c * 16) = v;
-            }
+    };
+    // Activation slab -> LDS without passing through registers (global_load_lds_dwordx4): each
+    // instruction fills 64 consecutive 16-byte LDS slots, one per lane, from per-lane addresses.
+    // Slot (row, cs) holds k-piece cs ^ f(row): the XOR swizzle makes the 16 rows an MFMA A
+    // operand read touches fall into 16 different bank groups (row stride is 256 / 128 bytes).
+    // per-thread byte offsets (inside the token tile) of the pieces this thread requests: constant
+    // over the slabs, so a slab's request is one uniform base plus these 32-bit offsets
+    uint32_t xoff[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int S = i * 256 + tid;
+        const int row = S / PER_ROW, cs = S % PER_ROW;
+        const int c = cs ^ swz(row);
+        int m = m0 + row;
+        m = m < a.tokens ? m : a.tokens - 1;          // rows past the end are never stored
+        xoff[i] = (uint32_t)(m - m0) * (uint32_t)a.in * XB + c * 16;
+    }
+    const unsigned char *xtile = reinterpret_cast<const unsigned char *>(a.X) + (int64_t)m0 * a.in * XB;
+    auto stage_x = [&](int g, unsigned char *buf) {
+        const unsigned char *base = xtile + (int64_t)g * GOQ_N * XB;
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(base + xoff[i]),
+                (__attribute__((address_space(3))) void *)(buf + (i * 256 + wave * 64) * 16), 16, 0, 0);
+    };
+
+    // slab 0 is staged up front; afterwards the next slab's weights and activations are requested
+    // from HBM before the current slab's MFMAs (activations land in the other LDS buffer)
+    uint4 wd[NS], meta[NS], wdn[NS], metan[NS];
+    load_weights(0, wd, meta);
+    stage_x(0, xs0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    for (int g = 0; g < a.gn; ++g) {
+        const unsigned char *xs = (g & 1) ? xs1 : xs0;
+        if (g + 1 < a.gn) {
+            load_weights(g + 1, wdn, metan);
+            stage_x(g + 1, (g & 1) ? xs0 : xs1);
         }
-        __syncthreads();
 
         // ---- coefficient pair of this lane's column in every column tile
         float c1[NS], c2[NS];
@@ -216,52 +253,69 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs a)
             c2[j] = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
         }
 
-        // ---- the slab, one column tile at a time (keeps only one tile column of P1, P2 live)
+        // ---- the slab's MFMAs: every A operand read from LDS feeds the b1 and b2 MFMAs of both
+        //      column tiles
+        AccT P1[MS][NS], P2[MS][NS];
 #pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            AccT P1[MS], P2[MS];
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            if constexpr (ACT == 0) {
+                f16x8 B1[NS], B2[NS];
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                if constexpr (ACT == 0) {
+                for (int j = 0; j < NS; ++j) {
                     const uint32_t w = ks == 0 ? wd[j].x : ks == 1 ? wd[j].y : ks == 2 ? wd[j].z : wd[j].w;
                     uint32_t l1, h1, l2, h2;
                     decode_pair<BW, ACT>(w, meta[j], ks, xtab, l1, h1, l2, h2);
-                    const f16x8 B1 = widen8(l1, h1);
-                    const f16x8 B2 = widen8(l2, h2);
+                    B1[j] = widen8(l1, h1);
+                    B2[j] = widen8(l2, h2);
+                }
 #pragma unroll
-                    for (int i = 0; i < MS; ++i) {
-                        // A operand: token 16 i + ln, k = 8 (4 lh + ks) .. + 7 of the slab
-                        const f16x8 A = *reinterpret_cast<const f16x8 *>(xs + (16 * i + ln) * ROWB + (4 * lh + ks) * 16);
-                        const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-                        P1[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B1, ks == 0 ? z : P1[i], 0, 0, 0);
-                        P2[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B2, ks == 0 ? z : P2[i], 0, 0, 0);
+                for (int i = 0; i < MS; ++i) {
+                    // A operand: token 16 i + ln, k = 8 (4 lh + ks) .. + 7 of the slab
+                    const f16x8 A = *reinterpret_cast<const f16x8 *>(xs + (16 * i + ln) * ROWB + (((4 * lh + ks) ^ swz(16 * i + ln)) * 16));
+                    const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < NS; ++j) {
+                        P1[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B1[j], ks == 0 ? z : P1[i][j], 0, 0, 0);
+                        P2[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B2[j], ks == 0 ? z : P2[i][j], 0, 0, 0);
                     }
-                } else {
+                }
+            } else {
+                i32x4 B1[NS], B2[NS];
+#pragma unroll
+                for (int j = 0; j < NS; ++j) {
                     const uint32_t wa = ks == 0 ? wd[j].x : wd[j].z;
                     const uint32_t wb = ks == 0 ? wd[j].y : wd[j].w;
                     uint32_t l1, h1, l2, h2, l3, h3, l4, h4;
                     decode_pair<BW, ACT>(wa, meta[j], 2 * ks, xtab, l1, h1, l2, h2);
                     decode_pair<BW, ACT>(wb, meta[j], 2 * ks + 1, xtab, l3, h3, l4, h4);
-                    const i32x4 B1 = i32x4{(int)l1, (int)h1, (int)l3, (int)h3};
-                    const i32x4 B2 = i32x4{(int)l2, (int)h2, (int)l4, (int)h4};
+                    B1[j] = i32x4{(int)l1, (int)h1, (int)l3, (int)h3};
+                    B2[j] = i32x4{(int)l2, (int)h2, (int)l4, (int)h4};
+                }
 #pragma unroll
-                    for (int i = 0; i < MS; ++i) {
-                        // A operand: token 16 i + ln, k = 32 lh + 16 ks .. + 15 of the slab
-                        const i32x4 A = *reinterpret_cast<const i32x4 *>(xs + (16 * i + ln) * ROWB + 32 * lh + 16 * ks);
-                        const i32x4 z = i32x4{0, 0, 0, 0};
-                        P1[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B1, ks == 0 ? z : P1[i], 0, 0, 0);
-                        P2[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B2, ks == 0 ? z : P2[i], 0, 0, 0);
+                for (int i = 0; i < MS; ++i) {
+                    // A operand: token 16 i + ln, k = 32 lh + 16 ks .. + 15 of the slab
+                    const i32x4 A = *reinterpret_cast<const i32x4 *>(xs + (16 * i + ln) * ROWB + (((2 * lh + ks) ^ swz(16 * i + ln)) * 16));
+                    const i32x4 z = i32x4{0, 0, 0, 0};
+#pragma unroll
+                    for (int j = 0; j < NS; ++j) {
+                        P1[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B1[j], ks == 0 ? z : P1[i][j], 0, 0, 0);
+                        P2[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B2[j], ks == 0 ? z : P2[i][j], 0, 0, 0);
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);   // keep the k-steps (and column tiles) in order
             }
-            // ---- coefficient rescale, once per slab, outside the dot-product loop (H5)
+#ifdef GOQ_GEMM_SCHEDBAR
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+        }
+        // ---- coefficient rescale, once per slab, outside the dot-product loop (H5)
 #pragma unroll
-            for (int i = 0; i < MS; ++i) {
+        for (int i = 0; i < MS; ++i)
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    Yacc[i][j][v] = fmaf(c1[j], (float)P1[i][v], Yacc[i][j][v]);
-                    Yacc[i][j][v] = fmaf(c2[j], (float)P2[i][v], Yacc[i][j][v]);
+                    Yacc[i][j][v] = fmaf(c1[j], (float)P1[i][j][v], Yacc[i][j][v]);
+                    Yacc[i][j][v] = fmaf(c2[j], (float)P2[i][j][v], Yacc[i][j][v]);
                 }
                 if constexpr (PART) {
                     // exact int32 slab partials [tokens][out][in/128][2] (verification output)
@@ -271,11 +325,16 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(GemmArgs a)
                     for (int v = 0; v < 4; ++v) {
                         const int m = m0 + 16 * i + 4 * lh + v;
                         if (m < a.tokens && n < a.out)
-                            *reinterpret_cast<int2 *>(pp + (int64_t)v * a.out * a.gn * 2) = make_int2(P1[i][v], P2[i][v]);
+                            *reinterpret_cast<int2 *>(pp + (int64_t)v * a.out * a.gn * 2) = make_int2(P1[i][j][v], P2[i][j][v]);
                     }
                 }
             }
+        if (g + 1 < a.gn) {
+#pragma unroll
+            for (int j = 0; j < NS; ++j) { wd[j] = wdn[j]; meta[j] = metan[j]; }
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next slab's activations are in LDS
+        __syncthreads();
     }
 
     // ---- store the tile (H6): lane holds Y[m0 + 16 i + 4 lh + v][n0 + 16 j + ln]
