@@ -120,7 +120,9 @@ def bench_gemv(args, shapes, bw, name):
     # HBM traffic per launch from the committed counter runs (FETCH_SIZE + WRITE_SIZE, scaled), if present
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json.txt")) as fh:
-            res["roofline"]["traffic"] = json.load(fh)["gemv_kernel<3,0>"]["hbm_bytes_per_launch"]
+            t = json.load(fh)["gemv_kernel<3,0>"]
+            if t["workload"] == name:
+                res["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         pass
     if args.traffic_ref:
@@ -180,6 +182,64 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
                          "frac": round(tops / peak, 4), "traffic": None}}
 
 
+def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
+    """A GEMM workload on its own (BASELINE configs 3, 4 and the GEMM half of 5): one launch per
+    matrix per step; value = issued TOPS (4 M N K per matrix)."""
+    import torch
+    import paper_2605_26092_amd as goq
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    act = goq.A16 if act_name == "A16" else goq.A8
+    packed, canon = [], []
+    for idx, (_, out, inn) in enumerate(shapes):
+        q = goq_inputs.canonical_random(bw, out, inn, config_id=3, tensor_id=300 + idx)
+        canon.append(q)
+        pk = torch.empty(goq.packed_bytes(bw, out, inn), dtype=torch.uint8, device=dev)
+        d = [torch.from_numpy(q[k].view(np.int16) if q[k].dtype == np.uint16 else q[k]).to(dev)
+             for k in ("codes", "pattern", "signs", "c1", "c2")]
+        goq.pack(bw, out, inn, *d, pk)
+        torch.cuda.synchronize()
+        packed.append(pk)
+    g = bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=max(3, min(args.steps, 20)), warmup=2)
+    res = {
+        "metric": "PoT GEMV GB/s (% HBM peak) and GEMM TOPS (% MFMA peak), LLaMA-2-7B shapes",
+        "value": g["issued_TOPS"], "unit": g["roofline"]["unit"], "n_gpus": 1, "steps": max(3, min(args.steps, 20)),
+        "warmup": 2, "ms_per_step": g["ms_per_block"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if act_name == "A16" else "i8", "data": "synthetic",
+        "config": {"workload": name, "bw": bw, "act": act_name, "group": 128, "tokens": tokens, "matrices": len(shapes),
+                   "issued_ops_per_step": 4.0 * tokens * sum(o * i for _, o, i in shapes),
+                   "dense_equiv_TOPS": g["dense_equiv_TOPS"]},
+        "roofline": g["roofline"],
+    }
+    res["cpu_baseline"] = None if args.no_cpu else cpu_baseline_gemm(canon, shapes, bw, act_name, tokens)
+    return res
+
+
+def cpu_baseline_gemm(canon, shapes, bw, act_name, tokens):
+    """The oracle on a token slab of the first matrix (all outputs), issued-op rate."""
+    from oracle import goq_oracle as O
+    threads = min(O.max_threads(), os.cpu_count() or 1)
+    _, out, inn = shapes[0]
+    slab = 32 if act_name == "A16" else 64
+    if act_name == "A16":
+        x = goq_inputs.activations_a16(slab, inn, config_id=3, tensor_id=100, outlier_frac=0.01)
+    else:
+        x, sx = goq_inputs.activations_a8(slab, inn, config_id=4, tensor_id=200)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        if act_name == "A16":
+            O.gemm_a16(canon[0], x, threads=threads)
+        else:
+            O.gemm_a8(canon[0], x, sx, threads=threads)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > 10.0 or reps >= 200:
+            break
+    return {"value": round(4.0 * slab * out * inn * reps / el / 1e12, 5), "unit": "TOP/s (issued)", "cores": threads,
+            "kind": "oracle", "sample": "%d pass(es) over a %d-token slab of the first matrix (%dx%d), all outputs, %.1f s"
+            % (reps, slab, out, inn, el)}
+
+
 def cpu_baseline_gemv(canon, shapes, bw, alg_bytes):
     """The oracle, untuned, on the host cores: the same block of GEMVs."""
     from oracle import goq_oracle as O
@@ -203,7 +263,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c5_gemm"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -218,8 +278,16 @@ def main():
         res = bench_gemv(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "llama2-7b decoder block, 7 GEMVs, W3/A16, batch 1")
     elif args.workload == "c1_gemv":
         res = bench_gemv(args, [("l", 4096, 4096)], 3, "single 4096x4096 layer, W3/A16, batch 1")
-    else:
+    elif args.workload == "c5_gemv":
         res = bench_gemv(args, goq_inputs.LLAMA2_70B_LAYER, 3, "llama2-70b layer, 7 GEMVs, W3/A16, batch 1")
+    elif args.workload == "c3_gemm_w3":
+        res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W3/A16")
+    elif args.workload == "c3_gemm_w4":
+        res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 4, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W4/A16")
+    elif args.workload == "c4_gemm_a8":
+        res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 3, "A8", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W3/A8")
+    else:
+        res = bench_gemm_only(args, goq_inputs.LLAMA2_70B_LAYER, 3, "A16", 512, "llama2-70b layer GEMMs, 512 tokens, W3/A16")
     print(json.dumps(res))
 
 
