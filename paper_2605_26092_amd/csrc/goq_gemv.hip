@@ -1,34 +1,64 @@
 // goq_gemv / goq_gemv_batch: batch-1 dual-PoT layer output (Eq. 4 with one token).
 //
+// Why the matrix cores appear in a bandwidth-bound kernel.  A batch-1 product streams 4 (bw = 3)
+// or 5 (bw = 4) bits per weight and has to retire two multiply-accumulates per weight (b1 and b2).
+// On the vector ALU that is, all in, 3.5 lane-instructions per weight (decode, widen to fp16,
+// two-term dot products): more issue time than the HBM stream takes, so the vector ALU, not HBM,
+// was the limit.  Here the vector ALU only DECODES: a 3-bit code becomes, with one byte look-up
+// permute, the 8-bit float (E5M2) of its power of two -- E5M2 is exactly the high byte of the
+// fp16 value, and a power of two has no other nonzero byte -- and b2 is rebuilt from b1 by the
+// Theorem 1 exchange as one more byte permute plus a sign XOR (the "exchange multiplexer and
+// sign XOR gate" of Sec. 3.3, driven by the 6 stored metadata bits).  The multiply-accumulates
+// run on v_mfma_f32_16x16x128_f8f6f4 as a 16-row x 128-deep product per instruction:
+//
+//   B operand (weights): lane l = (column c = l % 16, k-group q = l / 16) supplies the 32 decoded
+//       weights k = 32 q .. 32 q + 31 of output row 16 j + c of the row block (j = 0..3: four
+//       instructions per basis cover the 64 rows of a row block times one macro-block).  That is
+//       exactly the 16-byte quad (chunk q, row 16 j + c) of the packed layout.
+//   A operand (activations): row i = digit i of the macro-block's 128 activations (rows 8..15
+//       are zero).  Activations are handed over as block fixed point, see stage_run.
+//   D[i][c] = sum_k digit_i(x_k) b[row c][k]: lane (c, q) receives digits 4q .. 4q + 3, so the
+//       slab dot product of a row is spread over two lanes and is put together once, when the
+//       row is stored.
+//
 // Work decomposition.  The unit of work is (row group, macro-block g): a ROW GROUP is 8 row
-// blocks of 64 output channels, one row block per wavefront of a 512-thread workgroup, one row
-// per lane.  The lane that owns row r loads that row's whole macro-block (CH coalesced 16-byte
-// quads, see goq_layout.h) and keeps both slab dot products P1, P2 and the coefficient pair in
-// its own registers, so a slab needs no cross-lane traffic; the coefficient rescale (H5) is two
-// FMAs per 128 weights, after the slab's dot products.
+// blocks of 64 output channels, one row block per wavefront of a 512-thread workgroup.  All units
+// of all problems of a launch form one linear sequence (problem, row group, g) cut into equal
+// contiguous pieces, one per workgroup (two workgroups per CU), so every workgroup streams the
+// same number of bytes whatever the matrix shapes are.  The coefficient rescale (H5) is two FMAs
+// per row and slab, after the slab's dot products.
 //
-// All units of all problems of a launch form one linear sequence (problem, row group, g) that
-// is cut into equal contiguous pieces, one per workgroup (two workgroups per CU), so the weight
-// stream of a workgroup is one long prefetched sequence and every workgroup gets the same
-// amount of work whatever the matrix shapes are.  Where a piece ends inside a row group the
-// partial y is combined with fp32 atomic adds (y zeroed by a fill kernel first); when fp16
-// output is requested the pieces are aligned to row groups instead and y is stored directly.
-//
-// Residual basis without rebuilding it: x . b2 = b1 . (T x), where T is the signed exchange
-// of the micro-block (Theorem 1).  T depends only on the micro-block's 6 metadata bits, and
-// x is shared by all rows, so the workgroup stages, per macro-block, the 64 possible T x for
-// each of the 16 micro-block positions in LDS (16 KiB for fp16 x) and a lane fetches the
-// variant its metadata selects with one 16-byte LDS read.  P1 uses x itself, which is uniform
-// across the wavefront (scalar registers).  Per micro-block a lane then spends: 2 byte-LUT
-// permutes (decode), 4 byte shuffles (widen to fp16), 8 two-term fp16 dot products.
+// Where a piece boundary falls inside a row group, each wavefront publishes the partial sums of
+// its 64 rows to a per-library scratch area and the LAST wavefront to arrive (an atomic counter
+// per boundary and row block) adds the parts in workgroup order and stores y: no zero-fill
+// pass, no floating-point atomics, and the result does not depend on timing.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <atomic>
 #include <type_traits>
 #include "goq_layout.h"
 #include "goq_decode.h"
 #include "goq_internal.h"
 
 namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int WAVES = 8;                 // wavefronts (= row blocks) per workgroup
+constexpr int NT = WAVES * 64;           // threads per workgroup
+constexpr int MAX_WG = 512;              // workgroups per launch (two per CU)
+constexpr int SW = 16;                   // units whose activation digits are resident in LDS
+constexpr int XG = 1024;                 // bytes of digits per macro-block: 4 k-groups x 8 digits x 32
+constexpr int XZ = 256;                  // zero bytes in front of the digit table
+constexpr int REGIONS = 8;               // scratch regions handed out round-robin to launches
+
+struct Region {
+    float partials[MAX_WG][2][NT];       // [workgroup][head | tail][row of the row group]
+    unsigned counters[MAX_WG][WAVES];    // arrivals per boundary (first contributor) and row block
+};
+__device__ __attribute__((aligned(256))) Region g_scratch[REGIONS];
 
 struct GemvProblem {
     const uint32_t *packed;
@@ -40,268 +70,150 @@ struct GemvProblem {
     int ytype;
     int rbn;         // row blocks
     int rgroups;     // row groups
-    int begin;       // first piece-space index of this problem (units, or row groups when !split)
+    int begin;       // first unit of this problem in the linear unit sequence
 };
 
 struct GemvArgs {
     int n;
-    int split;       // 1: pieces are unit ranges, combine with atomics; 0: pieces are whole row groups
-    int total;       // size of the piece space
+    int total;       // units in the launch
+    Region *scratch;
     GemvProblem p[GOQ_MAX_BATCH];
 };
 
-#ifndef GOQ_EXP_WAVES
-#define GOQ_EXP_WAVES 8
-#endif
-constexpr int WAVES = GOQ_EXP_WAVES;   // wavefronts (= row blocks) per workgroup
-
-// x is read-only for the whole kernel: reading it through the constant address space lets the
-// wave-uniform chunk of x live in scalar registers (s_load) instead of 64 identical lanes.
-typedef __attribute__((address_space(4))) uint32_t goq_const_u32;
-
-// Per-thread constants of the exchange variant v = pattern | signs << 2 this thread stages:
-// for output register t (elements 2t, 2t+1): which x register holds the partners, whether the
-// halves swap, and the sign mask (x'_i = +eta x_j for the lower index of a pair, -eta x_i for
-// the upper one).
-struct Variant {
-    int src[4];        // element index of the partner of element 2t (its register is src >> 1)
-    uint32_t swapsel;  // v_perm selector: identity or swap halves
-    uint32_t sign[4];  // fp16 sign masks for (element 2t, element 2t+1)
-    int8_t sgn8[8];    // +1 / -1 per element (int8 path)
-    int part[8];       // partner element
-};
-
-__device__ __forceinline__ Variant make_variant(int v)
+// Exchange table entry of variant v = pattern | signs << 2 (Theorem 1) for decoded BYTES:
+//   x, y : v_perm selectors, byte i of b2 = byte (i xor s) of b1
+//   z, w : 0x80 in the bytes whose sign flips: b2_i = -eta b1_j for the lower index of a
+//          pair, +eta b1_i for the upper one.
+__device__ __forceinline__ uint4 exchange_entry(int v)
 {
-    Variant V;
     const int s = (v & 3) + 1;
     const int sg = v >> 2;
+    uint32_t mlo = 0, mhi = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int j = i ^ s;
-        const int l = i < j ? i : j;                      // lower index of the pair
+        const int l = i < j ? i : j;
         // rank of the pair in ascending-lower-index order (the printed order of P_s)
         const int p = (s == 1) ? (l >> 1) : (s == 4) ? l : ((l & 1) | ((l >> 2) << 1));
         const int eta_neg = (sg >> p) & 1;
-        const int upper = i > j;
-        V.part[i] = j;
-        V.sgn8[i] = (int8_t)((eta_neg ^ upper) ? -1 : 1);
+        const int lower = i < j;
+        const uint32_t flip = (uint32_t)(eta_neg ^ lower) * 0x80u;
+        if (i < 4) mlo |= flip << (8 * i);
+        else mhi |= flip << (8 * (i - 4));
     }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        V.src[t] = (2 * t) ^ s;
-        V.sign[t] = (V.sgn8[2 * t] < 0 ? 0x00008000u : 0u) | (V.sgn8[2 * t + 1] < 0 ? 0x80000000u : 0u);
-    }
-    V.swapsel = (s & 1) ? 0x01000302u : 0x03020100u;
-    return V;
+    const uint32_t srep = (uint32_t)s * 0x01010101u;
+    return make_uint4(0x03020100u ^ srep, 0x07060504u ^ srep, mlo, mhi);
 }
+
+// What one lane holds of one unit: for j = 0..3 the quad (chunk q, row 16 j + c); for bw = 4
+// also, of row 16 j + c, the pattern word, the half of the sign words that covers chunk q, and
+// the coefficient word.
+template <int BW>
+struct UnitBuf {
+    uint4 q[4];
+    uint32_t mp[(BW == 4) ? 4 : 1], ms[(BW == 4) ? 4 : 1], mc[(BW == 4) ? 4 : 1];
+};
 
 template <int BW>
-__device__ __forceinline__ void load_block(const uint32_t *__restrict__ packed, int64_t gn, int64_t R,
-                                           int64_t g, int lane, uint4 (&d)[(BW == 3) ? 4 : 5])
+__device__ __forceinline__ void load_unit(const uint32_t *__restrict__ packed, int64_t gn, int64_t R, int64_t g,
+                                          int lane, UnitBuf<BW> &u)
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 *base = reinterpret_cast<const u32x4 *>(packed + goq_quad_index(CH, gn, R, g, 0, lane));
+    const int c = lane & 15, q = lane >> 4;
+    const uint32_t *base = packed + (R * gn + g) * (CH * GOQ_ROWS * 4);
+    const u32x4 *pq = reinterpret_cast<const u32x4 *>(base + q * (GOQ_ROWS * 4) + c * 4);
 #pragma unroll
-    for (int h = 0; h < CH; ++h) {
-#ifdef GOQ_EXP_NONT
-        const u32x4 v = base[h * GOQ_ROWS];
-#else
-        const u32x4 v = __builtin_nontemporal_load(base + h * GOQ_ROWS);   // streamed once: no reuse
-#endif
-        d[h] = make_uint4(v.x, v.y, v.z, v.w);
+    for (int j = 0; j < 4; ++j) {
+        const u32x4 v = __builtin_nontemporal_load(pq + 16 * j);       // streamed once: no reuse
+        u.q[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
-}
-
-// byte offset of the variant inside one micro-block position's table (16-byte entries for fp16 x,
-// 8-byte entries for int8 x)
-template <int BW, int ACT>
-__device__ __forceinline__ uint32_t variant_offset(uint32_t w, const uint4 &meta, int m)
-{
-    constexpr int SH = (ACT == 0) ? 4 : 3;
-#ifdef GOQ_EXP_UNIFORM_LDS
-    return 0;
-#endif
-    if constexpr (BW == 3) {
-        // a_0 (bits 6..7) a_1 (14..15) a_2 (22..23) -> contiguous 6-bit index at bits 18..23
-        const uint32_t t = w & 0x00C0C0C0u;
-        const uint32_t u = __umul24(t, 0x1041u);
-        return (u >> (18 - SH)) & (0x3Fu << SH);
-    } else {
-        const uint32_t pat = (meta.x >> (2 * m)) & 3u;
-        const uint32_t sg = ((m < 8 ? meta.y >> (4 * m) : meta.z >> (4 * (m - 8)))) & 15u;
-        return (pat | (sg << 2)) << SH;
-    }
-}
-
-// Staging of the exchanged copies T x of macro-block g, split in two so that the loads of x can
-// be issued a whole slab before they are needed.  Thread (wave, lane) produces variant `lane`
-// of micro-block positions wave and wave + 8.
-template <int ACT>
-struct StageRegs {
-    uint32_t v[16 / WAVES][(ACT == 0) ? 4 : 8];
-};
-
-template <int ACT>
-__device__ __forceinline__ void stage_load(StageRegs<ACT> &sr, const void *x, int g, int wave, const Variant &V)
-{
+    if constexpr (BW == 4) {
+        const uint32_t *pm = base + 4 * (GOQ_ROWS * 4) + c * 4;
 #pragma unroll
-    for (int j = 0; j < 16 / WAVES; ++j) {
-        const int m = wave + WAVES * j;
-        if constexpr (ACT == 0) {
-            const uint32_t *xm = reinterpret_cast<const uint32_t *>(x) + (int64_t)g * 64 + 4 * m;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) sr.v[j][t] = xm[V.src[t] >> 1];
-        } else {
-            const int8_t *xm = reinterpret_cast<const int8_t *>(x) + (int64_t)g * 128 + 8 * m;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) sr.v[j][i] = (uint32_t)(int32_t)xm[V.part[i]];
+        for (int j = 0; j < 4; ++j) {
+            u.mp[j] = __builtin_nontemporal_load(pm + 64 * j);
+            u.ms[j] = __builtin_nontemporal_load(pm + 64 * j + 1 + (q >> 1));
+            u.mc[j] = __builtin_nontemporal_load(pm + 64 * j + 3);
         }
     }
 }
 
+// ---- activation digits ----------------------------------------------------------------------
+// The 8-bit-float matrix instruction adds the products of 8 consecutive k on a grid that ends 13
+// binary places below the largest exponent sum of the 8 (measured); anything lower is cut off.
+// Floating-point pieces of x (own exponent per element) would therefore lose bits whenever a
+// micro-block mixes large and small activations.  So x is handed over as block FIXED point: for
+// each block of 32 activations that share an MFMA block scale, with largest exponent E, |x_k| is
+// written with 24 bits below 2^(E+1) -- every fp16 value within 2^13 of the block maximum exactly,
+// smaller ones truncated at 2^(E-23), the same footing as an fp32 sum -- and cut into 8 digits of
+// 3 bits.  Digit i of the block is an E5M2 operand (0..7 are exact in E5M2) with the block scale
+// 2^(E-2-3i), applied by the MFMA's per-lane E8M0 scale.  Inside a micro-block all products are
+// now (3-bit digit) x (power of two >= 2^-7): at most 13 binary places, so the instruction's grid
+// keeps every bit, and D = sum_k digit_k b_k is exact.
+//
+// Which 32 activations share a block scale is fixed by the instruction (measured): the scale a
+// lane of lane-group Q supplies covers, of the A row it holds, register halves (bytes 0..15 for
+// Q = 0, 1; bytes 16..31 for Q = 2, 3) of the two k-groups 2 (Q % 2) and 2 (Q % 2) + 1.  In
+// micro-blocks m = 0..15 of the macro-block that is block Q = {m : m / 8 == Q % 2, (m / 2) % 2 ==
+// Q / 2}, i.e. micro-blocks b, b+1, b+4, b+5 with b = 0, 8, 2, 10.
+//
+// One run = 8 consecutive activations (one micro-block), handled by one thread.  Digit table of a
+// macro-block: the 32 bytes of (k-group h, digit i) at h * 256 + i * 32; scale byte (E + 110) of
+// block Q at st[Q], where E + 15 is the largest biased fp16 exponent of the block (subnormals
+// count as 1).
 template <int ACT>
-__device__ __forceinline__ void stage_write(unsigned char *tb, const StageRegs<ACT> &sr, int wave, int lane,
-                                            const Variant &V)
+__device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, const void *x, int g, int r)
 {
-#pragma unroll
-    for (int j = 0; j < 16 / WAVES; ++j) {
-        const int m = wave + WAVES * j;
-        if constexpr (ACT == 0) {
-            uint4 e;
-            e.x = goq_perm(0u, sr.v[j][0], V.swapsel) ^ V.sign[0];
-            e.y = goq_perm(0u, sr.v[j][1], V.swapsel) ^ V.sign[1];
-            e.z = goq_perm(0u, sr.v[j][2], V.swapsel) ^ V.sign[2];
-            e.w = goq_perm(0u, sr.v[j][3], V.swapsel) ^ V.sign[3];
-            *reinterpret_cast<uint4 *>(tb + (m * 64 + lane) * 16) = e;
-        } else {
-            uint32_t lo = 0, hi = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lo |= (uint32_t)(uint8_t)(int8_t)(V.sgn8[i] * (int32_t)sr.v[j][i]) << (8 * i);
-                hi |= (uint32_t)(uint8_t)(int8_t)(V.sgn8[i + 4] * (int32_t)sr.v[j][i + 4]) << (8 * i);
-            }
-            *reinterpret_cast<uint2 *>(tb + (m * 64 + lane) * 8) = make_uint2(lo, hi);
-        }
-    }
-}
-
-// Operands of one pipeline stage = one chunk of 4 micro-blocks of one row: the chunk's x
-// (uniform, scalar registers) and the 4 exchanged copies the lane's metadata selects (LDS).
-template <int ACT>
-struct StageOps {
-    uint32_t xs[(ACT == 0) ? 16 : 8];
-    uint4 e[(ACT == 0) ? 4 : 2];
-};
-
-template <int BW, int ACT>
-__device__ __forceinline__ void fetch_stage(StageOps<ACT> &o, const uint4 &d, const uint4 &meta, int h,
-                                            const unsigned char *tb, const void *x, int g)
-{
-    const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
+    uint32_t v[4];
     if constexpr (ACT == 0) {
-        const goq_const_u32 *xs = reinterpret_cast<const goq_const_u32 *>((uintptr_t)x) + (int64_t)g * 64 + 16 * h;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o.xs[i] = xs[i];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            o.e[q] = *reinterpret_cast<const uint4 *>(tb + (4 * h + q) * 1024 +
-                                                     variant_offset<BW, ACT>(dw[q], meta, 4 * h + q));
+        const uint4 q = reinterpret_cast<const uint4 *>(x)[(int64_t)g * 16 + r];
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
     } else {
-        const goq_const_u32 *xs = reinterpret_cast<const goq_const_u32 *>((uintptr_t)x) + (int64_t)g * 32 + 8 * h;
+        const uint2 q = reinterpret_cast<const uint2 *>(x)[(int64_t)g * 16 + r];
+        const uint32_t b[2] = {q.x, q.y};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o.xs[i] = xs[i];
-        uint2 t[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            t[q] = *reinterpret_cast<const uint2 *>(tb + (4 * h + q) * 512 +
-                                                    variant_offset<BW, ACT>(dw[q], meta, 4 * h + q));
-        o.e[0] = make_uint4(t[0].x, t[0].y, t[1].x, t[1].y);
-        o.e[1] = make_uint4(t[2].x, t[2].y, t[3].x, t[3].y);
-    }
-}
-
-// H2..H4 for one chunk: decode, P1 += x . b1, P2 += (T x) . b1; gathers the coefficient bits.
-template <int BW, int ACT, typename AccT>
-__device__ __forceinline__ void compute_stage(const StageOps<ACT> &o, uint4 &d, AccT &P1, AccT &P2,
-                                              uint32_t &cw)
-{
-    // pin the chunk's decode to this pipeline stage (in place, no copies): without it the compiler
-    // hoists the pure decode arithmetic of all 16 micro-blocks to the top of the slab and runs out
-    // of registers
-    asm volatile("" : "+v"(d.x), "+v"(d.y), "+v"(d.z), "+v"(d.w));
-    const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t w = dw[q];
-        uint32_t lo, hi;
-        goq_decode_bytes<BW, ACT>(w, lo, hi);
-        if constexpr (ACT == 0) {
-            const uint32_t b0 = goq_widen01(lo), b1 = goq_widen23(lo);
-            const uint32_t b2 = goq_widen01(hi), b3 = goq_widen23(hi);
-            P1 = goq_dot2(b0, o.xs[4 * q + 0], P1);
-            P1 = goq_dot2(b1, o.xs[4 * q + 1], P1);
-            P1 = goq_dot2(b2, o.xs[4 * q + 2], P1);
-            P1 = goq_dot2(b3, o.xs[4 * q + 3], P1);
-#ifndef GOQ_EXP_NOP2
-            P2 = goq_dot2(b0, o.e[q].x, P2);
-            P2 = goq_dot2(b1, o.e[q].y, P2);
-            P2 = goq_dot2(b2, o.e[q].z, P2);
-            P2 = goq_dot2(b3, o.e[q].w, P2);
-#endif
-        } else {
-            const uint32_t ex = (q & 1) ? o.e[q >> 1].z : o.e[q >> 1].x;
-            const uint32_t ey = (q & 1) ? o.e[q >> 1].w : o.e[q >> 1].y;
-            P1 = goq_dot4(lo, o.xs[2 * q + 0], P1);
-            P1 = goq_dot4(hi, o.xs[2 * q + 1], P1);
-            P2 = goq_dot4(lo, ex, P2);
-            P2 = goq_dot4(hi, ey, P2);
+        for (int d = 0; d < 4; ++d) {
+            const int e0 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1)));
+            const int e1 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1) + 8));
+            const goq_half2 hv = {(_Float16)e0, (_Float16)e1};     // exact: |e| <= 128
+            v[d] = __builtin_bit_cast(uint32_t, hv);
         }
-        if constexpr (BW == 3) cw = __builtin_amdgcn_alignbit(cw, w, 30);
     }
-}
-
-// One slab of one row, software pipelined over its 4 chunks: the operands of chunk h+1 are
-// requested (scalar load of x, LDS reads of the exchanged copies) before chunk h is computed.
-// Ends with the coefficient rescale (H5): acc += c1 P1 + c2 P2.
-template <int BW, int ACT>
-__device__ __forceinline__ void slab(uint4 (&d)[(BW == 3) ? 4 : 5], const unsigned char *tb,
-                                     const void *x, int g, float &acc)
-{
-    using AccT = typename std::conditional<ACT == 0, float, int>::type;
-    uint32_t cw = 0;
-    uint4 meta = make_uint4(0, 0, 0, 0);
-    if constexpr (BW == 4) { meta = d[4]; cw = meta.w; }
-    AccT P1 = 0, P2 = 0;
-    // Scalar loads return out of order, so any use of one waits for ALL outstanding scalar and
-    // LDS requests.  Each stage therefore first touches its own operands (the wait lands here),
-    // then requests the next stage's, then computes.
-#define GOQ_TOUCH(o) asm volatile("" ::"s"((o).xs[0]), "v"((o).e[0].x))
-    StageOps<ACT> o0, o1;
-    fetch_stage<BW, ACT>(o0, d[0], meta, 0, tb, x, g);
-    GOQ_TOUCH(o0);
-    fetch_stage<BW, ACT>(o1, d[1], meta, 1, tb, x, g);
-    __builtin_amdgcn_sched_barrier(0);
-    compute_stage<BW, ACT>(o0, d[0], P1, P2, cw);
-    __builtin_amdgcn_sched_barrier(0);
-    GOQ_TOUCH(o1);
-    fetch_stage<BW, ACT>(o0, d[2], meta, 2, tb, x, g);
-    __builtin_amdgcn_sched_barrier(0);
-    compute_stage<BW, ACT>(o1, d[1], P1, P2, cw);
-    __builtin_amdgcn_sched_barrier(0);
-    GOQ_TOUCH(o0);
-    fetch_stage<BW, ACT>(o1, d[3], meta, 3, tb, x, g);
-    __builtin_amdgcn_sched_barrier(0);
-    compute_stage<BW, ACT>(o0, d[2], P1, P2, cw);
-    __builtin_amdgcn_sched_barrier(0);
-    GOQ_TOUCH(o1);
-    compute_stage<BW, ACT>(o1, d[3], P1, P2, cw);
-#undef GOQ_TOUCH
-    const float c1 = __half2float(__ushort_as_half((unsigned short)(cw & 0xffffu)));
-    const float c2 = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
-    acc = fmaf(c1, (float)P1, acc);
-    acc = fmaf(c2, (float)P2, acc);
+    // biased exponent (subnormals -> 1) and 11-bit significand of the 8 elements
+    int ex[8];
+    uint32_t mant[8];
+    int emax = 1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t hb = (v[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+        const int e = (hb >> 10) & 31;
+        ex[k] = e ? e : 1;
+        mant[k] = (hb & 1023u) | (e ? 1024u : 0u);
+        emax = max(emax, ex[k]);
+    }
+    emax = max(emax, __shfl_xor(emax, 1));              // runs r, r^1, r^4, r^5 form one scale block
+    emax = max(emax, __shfl_xor(emax, 4));
+    uint32_t fx[8];                                  // 24-bit fixed point, truncated
+#pragma unroll
+    for (int k = 0; k < 8; ++k) fx[k] = (mant[k] << 13) >> min(emax - ex[k], 31);
+    // sign bytes of elements 0..3 and 4..7
+    const uint32_t slo = goq_perm(v[1], v[0], 0x07050301u) & 0x80808080u;
+    const uint32_t shi = goq_perm(v[3], v[2], 0x07050301u) & 0x80808080u;
+    unsigned char *dst = xt + (r >> 2) * 256 + (r & 3) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t sl = 0, sh = 0;                     // digit i of the 8 elements, one per byte
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            sl |= ((fx[k] >> (21 - 3 * i)) & 7u) << (8 * k);
+            sh |= ((fx[k + 4] >> (21 - 3 * i)) & 7u) << (8 * k);
+        }
+        // E5M2 of 0..7: 00 3C 40 42 44 45 46 47
+        const uint32_t lo = goq_perm(0x47464544u, 0x42403C00u, sl) | slo;
+        const uint32_t hi = goq_perm(0x47464544u, 0x42403C00u, sh) | shi;
+        *reinterpret_cast<uint2 *>(dst + i * 32) = make_uint2(lo, hi);
+    }
+    if ((r & 5) == 0) st[(r & 2) | (r >> 3)] = (unsigned char)(emax + 110);
 }
 
 // Position in the linear unit sequence.
@@ -312,176 +224,301 @@ struct Cursor {
 __device__ __forceinline__ Cursor locate(const GemvArgs &a, int idx)
 {
     Cursor c;
-    if (idx >= a.total) { c.pi = a.n; c.rg = 0; c.g = 0; return c; }
     int pi = 0;
     while (pi + 1 < a.n && idx >= a.p[pi + 1].begin) ++pi;
     const int local = idx - a.p[pi].begin;
     c.pi = pi;
-    if (a.split) { c.rg = local / a.p[pi].gn; c.g = local % a.p[pi].gn; }
-    else { c.rg = local; c.g = 0; }
-    // the divisions run on the vector ALU: move the (uniform) results back to scalar registers
-    // so that all later cursor and address arithmetic is scalar
-    c.rg = __builtin_amdgcn_readfirstlane(c.rg);
-    c.g = __builtin_amdgcn_readfirstlane(c.g);
+    c.rg = local / a.p[pi].gn;
+    c.g = local % a.p[pi].gn;
     return c;
 }
 
-__device__ __forceinline__ bool same(const Cursor &a, const Cursor &b)
+// Digits of the units [u0, u0 + ns) of the sequence, unit s into table slot s.  Thread
+// (slot = tid / 16, run = tid % 16); ns <= SW = NT / 32.
+template <int ACT>
+__device__ __forceinline__ void stage_window(const GemvArgs &a, int u0, int ns, unsigned char *xt,
+                                             unsigned char *st, int tid)
 {
-    return a.pi == b.pi && a.rg == b.rg && a.g == b.g;
+    if (tid < ns * 16) {
+        const int slot = tid >> 4;
+        const Cursor c = locate(a, u0 + slot);
+        stage_run<ACT>(xt + slot * XG, st + slot * 4, a.p[c.pi].x, c.g, tid & 15);
+    }
 }
 
-// The few fields of a problem the streaming loop needs (kept in scalar registers); the output
-// side (y, out, sx, ytype) is re-read from the kernel arguments only when a row group is flushed.
-struct Stream {
-    const uint32_t *packed;
-    const void *x;
-    int gn, rbn, rgroups;
-};
-
-__device__ __forceinline__ Stream stream_of(const GemvArgs &a, int pi)
+// ---- one unit of one wavefront: 64 rows x one macro-block (H2..H5) --------------------------
+// buf: the lane's quads; vt: exchange table; A, sa: the macro-block's digits (this lane's A row
+// and k-group) and their block scale; cwx: this wavefront's 128-byte exchange area for
+// coefficient bytes; acc[j]: running sum of row 16 j + c over the digits this lane receives.
+template <int BW>
+__device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, const unsigned char *vt, const v8i &A, int sa,
+                                             unsigned char *cwx, int lane, float (&acc)[4])
 {
-    Stream s;
-    const uint64_t pk = (uint64_t)a.p[pi].packed, px = (uint64_t)a.p[pi].x;
-    s.packed = (const uint32_t *)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(pk >> 32)) << 32) |
-                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)pk));
-    s.x = (const void *)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(px >> 32)) << 32) |
-                         (uint32_t)__builtin_amdgcn_readfirstlane((int)px));
-    s.gn = __builtin_amdgcn_readfirstlane(a.p[pi].gn);
-    s.rbn = __builtin_amdgcn_readfirstlane(a.p[pi].rbn);
-    s.rgroups = __builtin_amdgcn_readfirstlane(a.p[pi].rgroups);
-    return s;
-}
-
-// One unit: prefetch the next unit's weights and x, compute this unit's slab, publish the next
-// unit's table.  Invariant on entry: tcur holds this unit's exchanged copies and every wave has
-// passed the barrier after they were written.  Returns false after the piece's last unit.
-template <int BW, int ACT>
-__device__ __forceinline__ bool gemv_unit(const GemvArgs &a, Cursor &cur, const Cursor &end, Stream &S,
-                                          uint4 (&bcur)[(BW == 3) ? 4 : 5], uint4 (&bnxt)[(BW == 3) ? 4 : 5],
-                                          unsigned char *tcur, unsigned char *tnxt, StageRegs<ACT> &sr,
-                                          const Variant &V, float &acc, int wave, int lane)
-{
-    Cursor nxt = cur;
-    if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
-    // the cursor is wave-uniform: keep it (and everything derived from it) in scalar registers
-    nxt.pi = __builtin_amdgcn_readfirstlane(nxt.pi);
-    nxt.rg = __builtin_amdgcn_readfirstlane(nxt.rg);
-    nxt.g = __builtin_amdgcn_readfirstlane(nxt.g);
-    const bool more = !same(nxt, end);
-    const bool new_problem = more && nxt.pi != cur.pi;
-    Stream Sn = S;
-    if (new_problem) Sn = stream_of(a, nxt.pi);
-    if (more) {
-        const int Rn = nxt.rg * WAVES + wave;
-#ifndef GOQ_EXP_NOMEM
-        if (Rn < Sn.rbn) load_block<BW>(Sn.packed, Sn.gn, Rn, nxt.g, lane, bnxt);
-#endif
-        stage_load<ACT>(sr, Sn.x, nxt.g, wave, V);
-    }
-    const int R = cur.rg * WAVES + wave;
-#ifdef GOQ_EXP_READONLY
-    if (R < S.rbn) {
-        uint32_t t = 0;
-        for (int h = 0; h < ((BW == 3) ? 4 : 5); ++h) t ^= bcur[h].x ^ bcur[h].y ^ bcur[h].z ^ bcur[h].w;
-        acc += (float)t;
-    }
-#else
-    if (R < S.rbn) slab<BW, ACT>(bcur, tcur, S.x, cur.g, acc);
-#endif
-    if (!more || nxt.rg != cur.rg || new_problem) {
-        // ---- reduce + store (H6): the lane owns the row, nothing to reduce inside the wave
-        const GemvProblem &P = a.p[cur.pi];
-        float v = acc;
-        if constexpr (ACT == 1) v *= P.sx[0] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
-        const int row = R * GOQ_ROWS + lane;
-        if (R < S.rbn && row < P.out) {
-            if (a.split) atomicAdd(reinterpret_cast<float *>(P.y) + row, v);
-            else if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row] = v;
-            else reinterpret_cast<__half *>(P.y)[row] = __float2half(v);
+    const int c = lane & 15, q = lane >> 4;
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t dw[4] = {buf.q[j].x, buf.q[j].y, buf.q[j].z, buf.q[j].w};
+        uint32_t mpq = 0, msq = 0;
+        if constexpr (BW == 4) {
+            mpq = buf.mp[j] >> (8 * q);                      // patterns of micro-blocks 4q .. 4q+3
+            msq = buf.ms[j] >> (16 * (q & 1));               // their sign nibbles
         }
-        acc = 0.f;
+        v8i B1, B2;
+        uint32_t cw = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t w = dw[k];
+            uint32_t lo, hi;
+            goq_decode_bytes<BW, 0>(w, lo, hi);                          // H2: code -> E5M2 byte
+            uint32_t eo;                                                 // 16 * (pattern | signs << 2)
+            if constexpr (BW == 3) {
+                // a_0 (bits 6..7) a_1 (14..15) a_2 (22..23) -> contiguous 6-bit index at bits 18..23
+                eo = (__umul24(w & 0x00C0C0C0u, 0x1041u) >> 14) & 0x3F0u;
+                cw = __builtin_amdgcn_alignbit(cw, w, 30);               // 2 coefficient bits per dword
+            } else {
+                eo = (((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 4;
+            }
+            const uint4 e = *reinterpret_cast<const uint4 *>(vt + eo);
+            B1[2 * k] = (int)lo;
+            B1[2 * k + 1] = (int)hi;
+            B2[2 * k] = (int)(goq_perm(hi, lo, e.x) ^ e.z);               // H4: exchange + sign XOR
+            B2[2 * k + 1] = (int)(goq_perm(hi, lo, e.y) ^ e.w);
+        }
+        // H3 / H4 accumulate: E5M2 x E5M2, fp32 accumulation; block scale sa on the activation
+        // side, 2^0 on the weight side
+        const v4f D1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B1, zero, 1, 1, 0, sa, 0, 127);
+        const v4f D2 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B2, zero, 1, 1, 0, sa, 0, 127);
+        // the coefficient word of row 16 j + c: bw = 3 spreads it over the row's 16 dwords, so the
+        // four lanes (c, 0..3) each hold one byte of it; they swap bytes through LDS
+        uint32_t cword;
+        if constexpr (BW == 3) {
+            // (LDS operations of one wavefront execute in order; the empty asm only keeps the
+            // compiler from moving the read above the write)
+            unsigned char *slot = cwx + (j & 1) * 64 + c * 4;
+            slot[3 - q] = (unsigned char)cw;
+            asm volatile("" ::: "memory");
+            cword = *reinterpret_cast<const uint32_t *>(slot);
+        } else {
+            cword = buf.mc[j];
+        }
+        // H5: coefficient rescale, once per slab, outside the dot-product loop
+        const float P1 = (D1[0] + D1[1]) + (D1[2] + D1[3]);
+        const float P2 = (D2[0] + D2[1]) + (D2[2] + D2[3]);
+        const float c1 = __half2float(__ushort_as_half((unsigned short)(cword & 0xffffu)));
+        const float c2 = __half2float(__ushort_as_half((unsigned short)(cword >> 16)));
+        acc[j] = fmaf(c1, P1, acc[j]);
+        acc[j] = fmaf(c2, P2, acc[j]);
     }
-    if (more) {
-        stage_write<ACT>(tnxt, sr, wave, lane, V);
-#ifndef GOQ_EXP_NOBARRIER
-        __syncthreads();
+}
+
+// first unit of workgroup b's piece
+__device__ __forceinline__ int piece_begin(int total, int nwg, int b)
+{
+    return (int)((int64_t)total * b / nwg);
+}
+
+// the workgroup whose piece holds unit u
+__device__ __forceinline__ int piece_of(int total, int nwg, int u)
+{
+    return (int)((((int64_t)u + 1) * nwg + total - 1) / total) - 1;
+}
+
+// H6 for the 64 rows of one wavefront: acc[j] of lanes (c, 0) and (c, 1) add up to the sum of row
+// 16 j + c over the units [max(u0, i0), min(u1, i1)) of its row group.
+template <int ACT>
+__device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, float (&acc)[4], int i0, int i1,
+                                      int nwg, int wave, int lane)
+{
+    const GemvProblem &P = a.p[cur.pi];
+    const int u0 = P.begin + cur.rg * P.gn, u1 = u0 + P.gn;
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v[j] = acc[j] + __shfl_xor(acc[j], 16);
+        if constexpr (ACT == 1) v[j] *= P.sx[0];
+    }
+    const bool owner = lane < 16;                          // lane c stores rows 16 j + c
+    const int rl = wave * GOQ_ROWS + lane;                 // row inside the row group (j = 0)
+    const int row = cur.rg * (WAVES * GOQ_ROWS) + rl;
+    auto store = [&](int j, float s) {
+        if (row + 16 * j < P.out) {
+            if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row + 16 * j] = s;
+            else reinterpret_cast<__half *>(P.y)[row + 16 * j] = __float2half(s);
+        }
+    };
+#ifdef GOQ_EXP_NOFIX
+    if (true) {
+#else
+    if (i0 <= u0 && u1 <= i1) {                            // the whole row group was ours
 #endif
+        if (owner) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) store(j, v[j]);
+        }
+        return;
     }
-    cur = nxt;
-    S = Sn;
-    return more;
+    // partial: publish, count arrivals, the last arrival adds the parts in workgroup order.
+    // The parts are written and read with device-scope accesses and the counter is a device-scope
+    // atomic, so no cache write-back / invalidate fence is needed: a wavefront waits until its own
+    // part has been acknowledged, then counts itself in.
+    Region *S = a.scratch;
+    const int b = blockIdx.x;
+    if (owner) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __hip_atomic_store(&S->partials[b][i0 > u0 ? 0 : 1][rl + 16 * j], v[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const int bf = piece_of(a.total, nwg, u0), bl = piece_of(a.total, nwg, u1 - 1);
+    unsigned old = 0;
+    if (lane == 0) {
+        old = __hip_atomic_fetch_add(&S->counters[bf][wave], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == (unsigned)(bl - bf))
+            __hip_atomic_store(&S->counters[bf][wave], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    old = (unsigned)__builtin_amdgcn_readfirstlane((int)old);
+    if (old == (unsigned)(bl - bf) && owner) {
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int w = bf; w <= bl; ++w) {
+            const int slot = piece_begin(a.total, nwg, w) > u0 ? 0 : 1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                s[j] += __hip_atomic_load(&S->partials[w][slot][rl + 16 * j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) store(j, s[j]);
+    }
 }
 
 template <int BW, int ACT>
-__global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvArgs a)
+__global__ __launch_bounds__(NT, 2) void gemv_kernel(GemvArgs a)
 {
-    constexpr int CH = (BW == 3) ? 4 : 5;
-    constexpr int ENTRY = (ACT == 0) ? 16 : 8;                  // bytes per table entry
-    constexpr int TBL = 16 * 64 * ENTRY;                        // one macro-block's table
-    __shared__ __attribute__((aligned(16))) unsigned char table[2][TBL];
+    // zeros (A rows 8..15), then the digit table of the resident units and its block scales
+    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];
+    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];
+    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 16];
+    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 128];
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // this workgroup's piece [i0, i1) of the piece space
-    const int64_t nwg = gridDim.x;
-    const int i0 = __builtin_amdgcn_readfirstlane((int)((int64_t)a.total * blockIdx.x / nwg));
-    const int i1 = __builtin_amdgcn_readfirstlane((int)((int64_t)a.total * (blockIdx.x + 1) / nwg));
+    // this workgroup's piece [i0, i1) of the unit sequence
+    const int nwg = gridDim.x;
+    const int i0 = __builtin_amdgcn_readfirstlane(piece_begin(a.total, nwg, blockIdx.x));
+    const int i1 = __builtin_amdgcn_readfirstlane(piece_begin(a.total, nwg, blockIdx.x + 1));
     if (i0 >= i1) return;
+
     Cursor cur = locate(a, i0);
-    const Cursor end = locate(a, i1);
-    Stream S = stream_of(a, cur.pi);
+    cur.rg = __builtin_amdgcn_readfirstlane(cur.rg);
+    cur.g = __builtin_amdgcn_readfirstlane(cur.g);
 
-    const Variant V = make_variant(lane);
-    float acc = 0.f;
-    uint4 bufA[CH], bufB[CH];
+    // the first unit's weights are requested before anything else
+    UnitBuf<BW> bufA, bufB;
 #ifdef GOQ_EXP_NOMEM
-    for (int h = 0; h < CH; ++h)
-        bufA[h] = bufB[h] = make_uint4(lane * 0x01234567u, lane * 0x89abcdefu + h, lane ^ 0x5a5a5a5au, h * 0x11111111u);
+    for (int j = 0; j < 4; ++j) bufA.q[j] = bufB.q[j] = make_uint4(lane * 0x01234567u, lane * 0x89abcdefu + j, lane ^ 0x5a5a5a5au, j * 0x11111111u);
 #endif
-    StageRegs<ACT> sr;
-
     {
-        const int R = cur.rg * WAVES + wave;
-#ifndef GOQ_EXP_NOMEM
-        if (R < S.rbn) load_block<BW>(S.packed, S.gn, R, cur.g, lane, bufA);
-#endif
-        stage_load<ACT>(sr, S.x, cur.g, wave, V);
-        stage_write<ACT>(table[0], sr, wave, lane, V);
-        __syncthreads();
+        const GemvProblem &P = a.p[cur.pi];
+        load_unit<BW>(P.packed, P.gn, min(cur.rg * WAVES + wave, P.rbn - 1), cur.g, lane, bufA);
     }
-    while (true) {
-        if (!gemv_unit<BW, ACT>(a, cur, end, S, bufA, bufB, table[0], table[1], sr, V, acc, wave, lane)) break;
-        if (!gemv_unit<BW, ACT>(a, cur, end, S, bufB, bufA, table[1], table[0], sr, V, acc, wave, lane)) break;
-    }
-}
 
-__global__ __launch_bounds__(256) void zero_kernel(GemvArgs a)
-{
-    const GemvProblem &P = a.p[blockIdx.y];
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < P.out; i += gridDim.x * blockDim.x)
-        reinterpret_cast<float *>(P.y)[i] = 0.f;
+    if (tid < 64) *reinterpret_cast<uint4 *>(vtab + tid * 16) = exchange_entry(tid);
+    if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
+
+    // A operand of this lane: row = lane % 16 (digit), k-group q = lane / 16
+    const int arow = lane & 15, q = lane >> 4;
+    const uint32_t abase = arow < 8 ? (uint32_t)(XZ + q * 256 + arow * 32) : 0u;
+    const uint32_t amask = arow < 8 ? ~0u : 0u;
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    int idx = i0;
+    // One unit: (re)stage the digits when the resident window is used up, request the next unit's
+    // weights (MORE), compute this unit, flush at the end of a row group.  The request is
+    // unconditional inside a MORE step -- a wavefront without rows of its own in the next row
+    // group re-reads that group's last row block -- so that the compiler's wait counts stay
+    // exact: this unit's registers wait for exactly the loads older than the new request.
+    auto step = [&](UnitBuf<BW> &bcur, UnitBuf<BW> &bnxt, auto more_tag) {
+        constexpr bool MORE = decltype(more_tag)::value;
+        const int slot = (idx - i0) % SW;
+        if (slot == 0) {
+            if (idx != i0) __syncthreads();                    // everyone is done with the old window
+            stage_window<ACT>(a, idx, min(SW, i1 - idx), xtab + XZ, stab, tid);
+            __syncthreads();
+        }
+        const GemvProblem &P = a.p[cur.pi];
+        const int gn = __builtin_amdgcn_readfirstlane(P.gn), rgroups = __builtin_amdgcn_readfirstlane(P.rgroups);
+        Cursor nxt = cur;
+        if (++nxt.g == gn) { nxt.g = 0; if (++nxt.rg == rgroups) { nxt.rg = 0; ++nxt.pi; } }
+        if constexpr (MORE) {
+            const GemvProblem &Pn = a.p[nxt.pi];
+#ifndef GOQ_EXP_NOMEM
+            load_unit<BW>(Pn.packed, Pn.gn, min(nxt.rg * WAVES + wave, Pn.rbn - 1), nxt.g, lane, bnxt);
+#endif
+        }
+        const int R = cur.rg * WAVES + wave;
+        const bool live = R < P.rbn;
+#ifdef GOQ_EXP_NOCOMPUTE
+        if (live) { for (int j = 0; j < 4; ++j) acc[j] += __builtin_bit_cast(float, bcur.q[j].x ^ bcur.q[j].y ^ bcur.q[j].z ^ bcur.q[j].w); }
+        if (false) {
+#else
+        if (live) {
+#endif
+            const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
+            const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
+            const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * arow;     // digit i sits 3 i places lower
+            compute_unit<BW>(bcur, vtab, A, sa, cwx + wave * 128, lane, acc);
+        }
+        if (!MORE || nxt.rg != cur.rg || nxt.pi != cur.pi) {
+            if (live) flush<ACT>(a, cur, acc, i0, i1, nwg, wave, lane);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = 0.f;
+        }
+        cur = nxt;
+        ++idx;
+    };
+    while (true) {
+        if (idx + 1 < i1) step(bufA, bufB, std::true_type{});
+        else { step(bufA, bufB, std::false_type{}); break; }
+        if (idx + 1 < i1) step(bufB, bufA, std::true_type{});
+        else { step(bufB, bufA, std::false_type{}); break; }
+    }
 }
 
 template <int BW, int ACT>
 int launch(hipStream_t st, const GemvArgs &a, int nwg)
 {
-    if (a.split) hipLaunchKernelGGL(zero_kernel, dim3(8, a.n), dim3(256), 0, st, a);
-    hipLaunchKernelGGL((gemv_kernel<BW, ACT>), dim3(nwg), dim3(WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL((gemv_kernel<BW, ACT>), dim3(nwg), dim3(NT), 0, st, a);
     return goq_check_launch("goq_gemv");
+}
+
+// device address of the scratch regions, looked up once per device
+Region *scratch_base()
+{
+    constexpr int MAXDEV = 64;
+    static std::atomic<Region *> base[MAXDEV];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAXDEV) return nullptr;
+    Region *p = base[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_scratch)) != hipSuccess || !sym) return nullptr;
+        p = reinterpret_cast<Region *>(sym);
+        base[dev].store(p, std::memory_order_release);
+    }
+    return p;
 }
 
 }  // namespace
 
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs)
 {
+    if (bw == 4 && act == GOQ_A8)
+        return goq_set_error(GOQ_EUNSUPPORTED, "goq_gemv: bw=4 with int8 activations is not implemented");
     GemvArgs a;
     a.n = n;
-    a.split = 1;
-    for (int i = 0; i < n; ++i)
-        if (descs[i].ytype != GOQ_F32) a.split = 0;     // fp16 y cannot take atomic partial sums
-    int total = 0;
+    int64_t total = 0;
     for (int i = 0; i < n; ++i) {
         GemvProblem &P = a.p[i];
         P.packed = (const uint32_t *)descs[i].packed;
@@ -493,19 +530,22 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
         P.ytype = descs[i].ytype;
         P.rbn = (int)goq_row_blocks(descs[i].out);
         P.rgroups = (P.rbn + WAVES - 1) / WAVES;
-        P.begin = total;
-        total += a.split ? P.rgroups * P.gn : P.rgroups;
+        P.begin = (int)total;
+        total += (int64_t)P.rgroups * P.gn;
+        if (total > 0x3fffffff) return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
     }
     for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].begin = 0x7fffffff; }
-    a.total = total;
-    // two 512-thread workgroups per CU fill the register file (4 wavefronts per SIMD)
-    int nwg = 2 * 256;
-#ifdef GOQ_EXP_NWG
-    nwg = GOQ_EXP_NWG;
-#endif
-    if (nwg > total) nwg = total;
+    a.total = (int)total;
+    // Scratch for row groups cut by a piece boundary.  Launches take the regions round-robin, so
+    // up to REGIONS launches may be in flight (on different streams) without sharing one.
+    static std::atomic<unsigned> ticket{0};
+    Region *base = scratch_base();
+    if (!base) return goq_set_error(GOQ_EHIP, "goq_gemv: cannot resolve the scratch area on this device");
+    a.scratch = base + ticket.fetch_add(1, std::memory_order_relaxed) % REGIONS;
+    // two 512-thread workgroups per CU (4 wavefronts per SIMD)
+    int nwg = MAX_WG;
+    if (nwg > a.total) nwg = a.total;
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, nwg);
     if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a, nwg);
-    if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, a, nwg);
-    return goq_set_error(GOQ_EUNSUPPORTED, "goq_gemv: bw=4 with int8 activations is not implemented");
+    return launch<4, 0>(st, a, nwg);
 }
