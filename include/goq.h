@@ -76,10 +76,15 @@ int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed
 /* Batch-1 layer output (Eq. 4 with one token).
  *   act = GOQ_A16: x is fp16 [in], sx must be NULL.
  *   act = GOQ_A8 : x is int8 [in], sx points to one fp32 scale (device).
- *   y is [out] of ytype.  The two slab dot products run on shifts/exponent adds (PoT operands
- *   decoded to native fp16 / int8), accumulate in fp32 / int32; coefficients are applied per
- *   slab in fp32.  Results are deterministic for GOQ_F16 output; GOQ_F32 output may use fp32
- *   atomic accumulation across slabs (summation order not fixed). */
+ *   y is [out] of ytype.  The PoT codes are decoded to 8-bit floats (a power of two is exact in
+ *   E5M2) and b2 is rebuilt from b1 by a byte permute and a sign flip; the two slab dot products
+ *   run on the 8-bit-float matrix instruction against x written as block fixed point (24 bits
+ *   below the largest exponent of each 32-activation block: exact for int8 x, and for fp16 x up
+ *   to a truncation at 2^-24 of the block maximum), accumulate in fp32; coefficients are applied
+ *   per slab in fp32.  Results are deterministic (no floating-point atomics).  Row groups split
+ *   over several workgroups are combined through a library-owned scratch area on the device
+ *   (16 MiB, 8 regions handed out round-robin): at most 8 goq_gemv / goq_gemv_batch launches
+ *   may be in flight at the same time on one device. */
 int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in,
              const void *packed, const void *x, const float *sx, void *y, int ytype);
 

@@ -40,6 +40,7 @@
 #include "goq_decode.h"
 #include "goq_internal.h"
 
+
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -332,43 +333,35 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
 {
     const GemvProblem &P = a.p[cur.pi];
     const int u0 = P.begin + cur.rg * P.gn, u1 = u0 + P.gn;
-    float v[4];
+    // lane l takes over row l of the row block: the sum of row 16 j + c sits in lanes c and c + 16
+    float mine = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        v[j] = acc[j] + __shfl_xor(acc[j], 16);
-        if constexpr (ACT == 1) v[j] *= P.sx[0];
+        const float t = acc[j] + __shfl_xor(acc[j], 16);
+        const float r = __shfl(t, lane & 15);
+        if ((lane >> 4) == j) mine = r;
     }
-    const bool owner = lane < 16;                          // lane c stores rows 16 j + c
-    const int rl = wave * GOQ_ROWS + lane;                 // row inside the row group (j = 0)
+    if constexpr (ACT == 1) mine *= P.sx[0];
+    const int rl = wave * GOQ_ROWS + lane;                 // row inside the row group
     const int row = cur.rg * (WAVES * GOQ_ROWS) + rl;
-    auto store = [&](int j, float s) {
-        if (row + 16 * j < P.out) {
-            if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row + 16 * j] = s;
-            else reinterpret_cast<__half *>(P.y)[row + 16 * j] = __float2half(s);
+    auto store = [&](float s) {
+        if (row < P.out) {
+            if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row] = s;
+            else reinterpret_cast<__half *>(P.y)[row] = __float2half(s);
         }
     };
-#ifdef GOQ_EXP_NOFIX
-    if (true) {
-#else
     if (i0 <= u0 && u1 <= i1) {                            // the whole row group was ours
-#endif
-        if (owner) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) store(j, v[j]);
-        }
+        store(mine);
         return;
     }
     // partial: publish, count arrivals, the last arrival adds the parts in workgroup order.
     // The parts are written and read with device-scope accesses and the counter is a device-scope
     // atomic, so no cache write-back / invalidate fence is needed: a wavefront waits until its own
-    // part has been acknowledged, then counts itself in.
+    // part has been acknowledged, then counts itself in.  Of the contributors bf..bl only the
+    // first can hold the row group as the tail of its piece (slot 1); for the others it is the head.
     Region *S = a.scratch;
     const int b = blockIdx.x;
-    if (owner) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __hip_atomic_store(&S->partials[b][i0 > u0 ? 0 : 1][rl + 16 * j], v[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    __hip_atomic_store(&S->partials[b][i0 > u0 ? 0 : 1][rl], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     const int bf = piece_of(a.total, nwg, u0), bl = piece_of(a.total, nwg, u1 - 1);
     unsigned old = 0;
@@ -378,21 +371,23 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
             __hip_atomic_store(&S->counters[bf][wave], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     old = (unsigned)__builtin_amdgcn_readfirstlane((int)old);
-    if (old == (unsigned)(bl - bf) && owner) {
-        float s[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int w = bf; w <= bl; ++w) {
-            const int slot = piece_begin(a.total, nwg, w) > u0 ? 0 : 1;
+    if (old == (unsigned)(bl - bf)) {
+        float s = __hip_atomic_load(&S->partials[bf][1][rl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int w = bf + 1; w <= bl; w += 8) {            // eight independent loads at a time
+            float t[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                s[j] += __hip_atomic_load(&S->partials[w][slot][rl + 16 * j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int i = 0; i < 8; ++i)
+                t[i] = __hip_atomic_load(&S->partials[min(w + i, bl)][0][rl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (w + i <= bl) s += t[i];
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) store(j, s[j]);
+        store(s);
     }
 }
 
 template <int BW, int ACT>
-__global__ __launch_bounds__(NT, 2) void gemv_kernel(GemvArgs a)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemv_kernel(GemvArgs a)
 {
     // zeros (A rows 8..15), then the digit table of the resident units and its block scales
     __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];
@@ -416,9 +411,6 @@ __global__ __launch_bounds__(NT, 2) void gemv_kernel(GemvArgs a)
 
     // the first unit's weights are requested before anything else
     UnitBuf<BW> bufA, bufB;
-#ifdef GOQ_EXP_NOMEM
-    for (int j = 0; j < 4; ++j) bufA.q[j] = bufB.q[j] = make_uint4(lane * 0x01234567u, lane * 0x89abcdefu + j, lane ^ 0x5a5a5a5au, j * 0x11111111u);
-#endif
     {
         const GemvProblem &P = a.p[cur.pi];
         load_unit<BW>(P.packed, P.gn, min(cur.rg * WAVES + wave, P.rbn - 1), cur.g, lane, bufA);
@@ -453,18 +445,11 @@ __global__ __launch_bounds__(NT, 2) void gemv_kernel(GemvArgs a)
         if (++nxt.g == gn) { nxt.g = 0; if (++nxt.rg == rgroups) { nxt.rg = 0; ++nxt.pi; } }
         if constexpr (MORE) {
             const GemvProblem &Pn = a.p[nxt.pi];
-#ifndef GOQ_EXP_NOMEM
             load_unit<BW>(Pn.packed, Pn.gn, min(nxt.rg * WAVES + wave, Pn.rbn - 1), nxt.g, lane, bnxt);
-#endif
         }
         const int R = cur.rg * WAVES + wave;
         const bool live = R < P.rbn;
-#ifdef GOQ_EXP_NOCOMPUTE
-        if (live) { for (int j = 0; j < 4; ++j) acc[j] += __builtin_bit_cast(float, bcur.q[j].x ^ bcur.q[j].y ^ bcur.q[j].z ^ bcur.q[j].w); }
-        if (false) {
-#else
         if (live) {
-#endif
             const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
             const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
             const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * arow;     // digit i sits 3 i places lower
