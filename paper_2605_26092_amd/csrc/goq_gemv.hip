@@ -77,6 +77,7 @@ struct GemvProblem {
 struct GemvArgs {
     int n;
     int total;       // units in the launch
+    int pq, pr;      // total / workgroups, total % workgroups
     Region *scratch;
     GemvProblem p[GOQ_MAX_BATCH];
 };
@@ -121,15 +122,19 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ packed, i
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
     const int c = lane & 15, q = lane >> 4;
-    const uint32_t *base = packed + (R * gn + g) * (CH * GOQ_ROWS * 4);
-    const u32x4 *pq = reinterpret_cast<const u32x4 *>(base + q * (GOQ_ROWS * 4) + c * 4);
+    // (explicitly a global-memory pointer: a generic one would turn the loads into flat loads,
+    // which the LDS wait counter has to wait for as well)
+    typedef const __attribute__((address_space(1))) uint32_t *gptr;
+    typedef const __attribute__((address_space(1))) u32x4 *gptr4;
+    gptr base = (gptr)packed + (R * gn + g) * (CH * GOQ_ROWS * 4);
+    gptr4 pq = (gptr4)(base + q * (GOQ_ROWS * 4) + c * 4);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const u32x4 v = __builtin_nontemporal_load(pq + 16 * j);       // streamed once: no reuse
         u.q[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
     if constexpr (BW == 4) {
-        const uint32_t *pm = base + 4 * (GOQ_ROWS * 4) + c * 4;
+        gptr pm = base + 4 * (GOQ_ROWS * 4) + c * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             u.mp[j] = __builtin_nontemporal_load(pm + 64 * j);
@@ -234,6 +239,25 @@ __device__ __forceinline__ Cursor locate(const GemvArgs &a, int idx)
     return c;
 }
 
+// The few fields of a problem the streaming loop needs, read from the kernel arguments once per
+// problem and kept in scalar registers.
+struct Stream {
+    const uint32_t *packed;
+    int gn, rbn, rgroups;
+};
+
+__device__ __forceinline__ Stream stream_of(const GemvArgs &a, int pi)
+{
+    Stream s;
+    const uint64_t pk = (uint64_t)a.p[pi].packed;
+    s.packed = (const uint32_t *)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(pk >> 32)) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)pk));
+    s.gn = __builtin_amdgcn_readfirstlane(a.p[pi].gn);
+    s.rbn = __builtin_amdgcn_readfirstlane(a.p[pi].rbn);
+    s.rgroups = __builtin_amdgcn_readfirstlane(a.p[pi].rgroups);
+    return s;
+}
+
 // Digits of the units [u0, u0 + ns) of the sequence, unit s into table slot s.  Thread
 // (slot = tid / 16, run = tid % 16); ns <= SW = NT / 32.
 template <int ACT>
@@ -272,13 +296,14 @@ __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, const unsig
             const uint32_t w = dw[k];
             uint32_t lo, hi;
             goq_decode_bytes<BW, 0>(w, lo, hi);                          // H2: code -> E5M2 byte
-            uint32_t eo;                                                 // 16 * (pattern | signs << 2)
+            uint32_t eo;                                                 // 64 * (pattern | signs << 2)
             if constexpr (BW == 3) {
-                // a_0 (bits 6..7) a_1 (14..15) a_2 (22..23) -> contiguous 6-bit index at bits 18..23
-                eo = (__umul24(w & 0x00C0C0C0u, 0x1041u) >> 14) & 0x3F0u;
+                // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
+                // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
+                eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, 0u, false);
                 cw = __builtin_amdgcn_alignbit(cw, w, 30);               // 2 coefficient bits per dword
             } else {
-                eo = (((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 4;
+                eo = (((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 6;
             }
             const uint4 e = *reinterpret_cast<const uint4 *>(vt + eo);
             B1[2 * k] = (int)lo;
@@ -313,23 +338,26 @@ __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, const unsig
     }
 }
 
+// The unit sequence is cut into nwg pieces: the first `pr` workgroups take pq + 1 units, the others
+// pq (pq = total / nwg and pr = total % nwg come from the host).
 // first unit of workgroup b's piece
-__device__ __forceinline__ int piece_begin(int total, int nwg, int b)
+__device__ __forceinline__ int piece_begin(const GemvArgs &a, int b)
 {
-    return (int)((int64_t)total * b / nwg);
+    return b * a.pq + min(b, a.pr);
 }
 
 // the workgroup whose piece holds unit u
-__device__ __forceinline__ int piece_of(int total, int nwg, int u)
+__device__ __forceinline__ int piece_of(const GemvArgs &a, int u)
 {
-    return (int)((((int64_t)u + 1) * nwg + total - 1) / total) - 1;
+    const int big = a.pr * (a.pq + 1);                      // units held by the larger pieces
+    return u < big ? u / (a.pq + 1) : a.pr + (u - big) / a.pq;
 }
 
 // H6 for the 64 rows of one wavefront: acc[j] of lanes (c, 0) and (c, 1) add up to the sum of row
 // 16 j + c over the units [max(u0, i0), min(u1, i1)) of its row group.
 template <int ACT>
 __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, float (&acc)[4], int i0, int i1,
-                                      int nwg, int wave, int lane)
+                                      int wave, int lane)
 {
     const GemvProblem &P = a.p[cur.pi];
     const int u0 = P.begin + cur.rg * P.gn, u1 = u0 + P.gn;
@@ -362,8 +390,8 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
     Region *S = a.scratch;
     const int b = blockIdx.x;
     __hip_atomic_store(&S->partials[b][i0 > u0 ? 0 : 1][rl], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int bf = piece_of(a, u0), bl = piece_of(a, u1 - 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    const int bf = piece_of(a.total, nwg, u0), bl = piece_of(a.total, nwg, u1 - 1);
     unsigned old = 0;
     if (lane == 0) {
         old = __hip_atomic_fetch_add(&S->counters[bf][wave], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -392,7 +420,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // zeros (A rows 8..15), then the digit table of the resident units and its block scales
     __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];
     __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];
-    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 16];
+    // exchange table: entry v at 64 v + 16 r, four copies r (a lane uses copy lane % 4)
+    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];
     __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 128];
 
     const int tid = threadIdx.x;
@@ -400,9 +429,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // this workgroup's piece [i0, i1) of the unit sequence
-    const int nwg = gridDim.x;
-    const int i0 = __builtin_amdgcn_readfirstlane(piece_begin(a.total, nwg, blockIdx.x));
-    const int i1 = __builtin_amdgcn_readfirstlane(piece_begin(a.total, nwg, blockIdx.x + 1));
+    const int i0 = __builtin_amdgcn_readfirstlane(piece_begin(a, blockIdx.x));
+    const int i1 = __builtin_amdgcn_readfirstlane(piece_begin(a, blockIdx.x + 1));
     if (i0 >= i1) return;
 
     Cursor cur = locate(a, i0);
@@ -411,12 +439,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 
     // the first unit's weights are requested before anything else
     UnitBuf<BW> bufA, bufB;
-    {
-        const GemvProblem &P = a.p[cur.pi];
-        load_unit<BW>(P.packed, P.gn, min(cur.rg * WAVES + wave, P.rbn - 1), cur.g, lane, bufA);
-    }
+    Stream S = stream_of(a, cur.pi);
+    load_unit<BW>(S.packed, S.gn, min(cur.rg * WAVES + wave, S.rbn - 1), cur.g, lane, bufA);
 
-    if (tid < 64) *reinterpret_cast<uint4 *>(vtab + tid * 16) = exchange_entry(tid);
+    if (tid < 256) *reinterpret_cast<uint4 *>(vtab + tid * 16) = exchange_entry(tid >> 2);
     if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
 
     // A operand of this lane: row = lane % 16 (digit), k-group q = lane / 16
@@ -439,28 +465,28 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
             stage_window<ACT>(a, idx, min(SW, i1 - idx), xtab + XZ, stab, tid);
             __syncthreads();
         }
-        const GemvProblem &P = a.p[cur.pi];
-        const int gn = __builtin_amdgcn_readfirstlane(P.gn), rgroups = __builtin_amdgcn_readfirstlane(P.rgroups);
         Cursor nxt = cur;
-        if (++nxt.g == gn) { nxt.g = 0; if (++nxt.rg == rgroups) { nxt.rg = 0; ++nxt.pi; } }
+        if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
+        Stream Sn = S;
         if constexpr (MORE) {
-            const GemvProblem &Pn = a.p[nxt.pi];
-            load_unit<BW>(Pn.packed, Pn.gn, min(nxt.rg * WAVES + wave, Pn.rbn - 1), nxt.g, lane, bnxt);
+            if (nxt.pi != cur.pi) Sn = stream_of(a, nxt.pi);
+            load_unit<BW>(Sn.packed, Sn.gn, min(nxt.rg * WAVES + wave, Sn.rbn - 1), nxt.g, lane, bnxt);
         }
         const int R = cur.rg * WAVES + wave;
-        const bool live = R < P.rbn;
+        const bool live = R < S.rbn;
         if (live) {
             const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
             const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
             const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * arow;     // digit i sits 3 i places lower
-            compute_unit<BW>(bcur, vtab, A, sa, cwx + wave * 128, lane, acc);
+            compute_unit<BW>(bcur, vtab + (lane & 3) * 16, A, sa, cwx + wave * 128, lane, acc);
         }
         if (!MORE || nxt.rg != cur.rg || nxt.pi != cur.pi) {
-            if (live) flush<ACT>(a, cur, acc, i0, i1, nwg, wave, lane);
+            if (live) flush<ACT>(a, cur, acc, i0, i1, wave, lane);
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[j] = 0.f;
         }
         cur = nxt;
+        S = Sn;
         ++idx;
     };
     while (true) {
@@ -530,6 +556,8 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     // two 512-thread workgroups per CU (4 wavefronts per SIMD)
     int nwg = MAX_WG;
     if (nwg > a.total) nwg = a.total;
+    a.pq = a.total / nwg;
+    a.pr = a.total % nwg;
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, nwg);
     if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a, nwg);
     return launch<4, 0>(st, a, nwg);
