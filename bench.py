@@ -76,6 +76,11 @@ def bench_gemv(args, shapes, bw, name):
     def step(i):
         goq.gemv_batch(bw, goq.A16, descs[i % copies], stream=stream)
 
+    # clock settle (part of set-up, untimed): the launches are tens of microseconds long, so the
+    # W warm-up steps alone end before the GPU's clock governor has reacted to the load
+    for i in range(args.settle):
+        step(i)
+    torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -112,6 +117,7 @@ def bench_gemv(args, shapes, bw, name):
         "config": {"workload": name, "bw": bw, "act": "A16", "group": 128, "matrices": len(shapes),
                    "weights": int(sum(o * i for _, o, i in shapes)), "algorithmic_bytes_per_step": int(alg_bytes),
                    "rotating_copies": copies, "launches_per_step": 1, "setup_s": round(setup_s, 1),
+                   "settle_launches": args.settle,
                    "cache_resident_GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
@@ -261,8 +267,10 @@ def cpu_baseline_gemv(canon, shapes, bw, alg_bytes):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--settle", type=int, default=3000,
+                    help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
     ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c5_gemm"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
