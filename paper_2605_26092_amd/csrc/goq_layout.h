@@ -4,9 +4,10 @@
 //
 // Unit of the layout: a ROW BLOCK of 64 consecutive output channels times one macro-block
 // (128 input channels).  It is stored as CH "chunks" of 1 KiB; chunk h holds, for every row
-// r = 0..63 of the block, one 16-byte quad at byte offset r*16.  A wavefront whose lane r
-// reads quad r of a chunk therefore issues one fully coalesced 1 KiB load, and lane r ends up
-// owning the whole macro-block of row r after CH loads.
+// r = 0..63 of the block, one 16-byte quad at byte offset r*16: 32 consecutive weights of the
+// row (four micro-blocks), which is one k-slice group of a matrix-core operand.  A wavefront
+// whose lanes read 16 consecutive quads of each of four chunks (or 64 of one) issues loads made
+// of full 256-byte runs, and the unit's bytes are each read exactly once.
 //
 //   dword index of (row block R, macro-block g, chunk h, row r, dword q)
 //        = ((((R * G_n + g) * CH + h) * 64 + r) * 4 + q            G_n = in / 128
