@@ -221,6 +221,71 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
     return res
 
 
+def bench_quantize(args, shapes, bw, name):
+    """The GEO quantizer on the device (goq_quantize): a step quantizes every matrix of the block.
+    Not the headline metric: reported in weights/s, with the HBM roofline of its own traffic
+    (2 B read + 1 B codes + 0.25 B metadata + 4/128 B coefficients written per weight)."""
+    import torch
+    import paper_2605_26092_amd as goq
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    bufs = []
+    for idx, (_, out, inn) in enumerate(shapes):
+        w = goq_inputs.weights(out, inn, config_id=6, tensor_id=idx)
+        bufs.append((out, inn, torch.from_numpy(w.view(np.int16)).to(dev),
+                     torch.empty((out, inn), dtype=torch.uint8, device=dev),
+                     torch.empty((out, inn // 8), dtype=torch.uint8, device=dev),
+                     torch.empty((out, inn // 8), dtype=torch.uint8, device=dev),
+                     torch.empty((out, inn // 128), dtype=torch.int16, device=dev),
+                     torch.empty((out, inn // 128), dtype=torch.int16, device=dev), w))
+    stream = torch.cuda.current_stream()
+    steps, warmup = max(3, min(args.steps, 20)), 2
+
+    def step():
+        for out, inn, wd, c, p, sg, c1, c2, _ in bufs:
+            goq.quantize(bw, out, inn, wd, c, p, sg, c1, c2, stream=stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    nw = sum(o * i for _, o, i in shapes)
+    nbytes = nw * (2 + 1 + 0.25 + 4.0 / 128)
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    res = {
+        "metric": "GEO quantizer, weights/s (LLaMA-2-7B block shapes)", "value": round(nw / (ms * 1e-3) / 1e9, 2),
+        "unit": "Gweights/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": name, "bw": bw, "group": 128, "matrices": len(shapes), "weights": int(nw),
+                   "llama2_7b_32_blocks_s": round(32 * ms * 1e-3, 4)},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "quantize_kernel<%d>" % bw},
+    }
+    if args.no_cpu:
+        res["cpu_baseline"] = None
+    else:
+        from oracle import goq_oracle as O
+        threads = min(O.max_threads(), os.cpu_count() or 1)
+        w = bufs[0][8][:1024]
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            O.quantize_geo(bw, w, threads=threads)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el > 10.0 or reps >= 50:
+                break
+        res["cpu_baseline"] = {"value": round(w.size * reps / el / 1e9, 5), "unit": "Gweights/s", "cores": threads,
+                               "kind": "oracle", "sample": "%d pass(es) over the first 1024 rows of the first matrix (%d weights), %.1f s"
+                               % (reps, w.size, el)}
+    return res
+
+
 def cpu_baseline_gemm(canon, shapes, bw, act_name, tokens):
     """The oracle on a token slab of the first matrix (all outputs), issued-op rate."""
     from oracle import goq_oracle as O
@@ -271,7 +336,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--settle", type=int, default=3000,
                     help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c5_gemm"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c5_gemm", "q_geo_w3", "q_geo_w4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -288,6 +353,9 @@ def main():
         res = bench_gemv(args, [("l", 4096, 4096)], 3, "single 4096x4096 layer, W3/A16, batch 1")
     elif args.workload == "c5_gemv":
         res = bench_gemv(args, goq_inputs.LLAMA2_70B_LAYER, 3, "llama2-70b layer, 7 GEMVs, W3/A16, batch 1")
+    elif args.workload in ("q_geo_w3", "q_geo_w4"):
+        bw = 3 if args.workload == "q_geo_w3" else 4
+        res = bench_quantize(args, goq_inputs.LLAMA2_7B_BLOCK, bw, "GEO quantization of a llama2-7b decoder block, W%d" % bw)
     elif args.workload == "c3_gemm_w3":
         res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W3/A16")
     elif args.workload == "c3_gemm_w4":

@@ -15,8 +15,8 @@ F16, F32 = 0, 1
 OK, EINVAL, ESHAPE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
 MAX_BATCH = 8
 
-EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_pack", "goq_unpack", "goq_gemv",
-           "goq_gemv_batch", "goq_gemm"]
+EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_pack", "goq_unpack",
+           "goq_gemv", "goq_gemv_batch", "goq_gemm"]
 
 
 class GoqError(RuntimeError):
@@ -42,6 +42,7 @@ def lib():
         L.goq_version.restype = i
         L.goq_last_error.restype = ctypes.c_char_p
         L.goq_packed_bytes.argtypes = [i, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
+        L.goq_quantize.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_pack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_unpack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_gemv.argtypes = [vp, i, i, i64, i64, vp, vp, vp, vp, i]
@@ -83,6 +84,11 @@ def packed_bytes(bw, out, inn):
     n = ctypes.c_size_t(0)
     _check(lib().goq_packed_bytes(bw, out, inn, ctypes.byref(n)))
     return n.value
+
+
+def quantize(bw, out, inn, w, codes, pattern, signs, c1, c2, stream=None):
+    _check(lib().goq_quantize(_stream(stream), bw, out, inn, _ptr(w), _ptr(codes), _ptr(pattern), _ptr(signs),
+                              _ptr(c1), _ptr(c2)))
 
 
 def pack(bw, out, inn, codes, pattern, signs, c1, c2, packed, stream=None):

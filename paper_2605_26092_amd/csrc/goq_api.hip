@@ -50,6 +50,18 @@ int goq_packed_bytes(int bw, int64_t out, int64_t in, size_t *bytes)
     return GOQ_OK;
 }
 
+int goq_quantize(void *stream, int bw, int64_t out, int64_t in, const uint16_t *w, uint8_t *codes,
+                 uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2)
+{
+    int rc = check_shape("goq_quantize", bw, out, in);
+    if (rc) return rc;
+    if (!w || !codes || !pattern || !signs || !c1 || !c2) return goq_set_error(GOQ_EINVAL, "goq_quantize: NULL pointer");
+    if (misaligned(w, 4) || misaligned(codes, 4) || misaligned(pattern, 4) || misaligned(signs, 4) ||
+        misaligned(c1, 2) || misaligned(c2, 2))
+        return goq_set_error(GOQ_EINVAL, "goq_quantize: w, codes, pattern and signs must be 4-byte aligned");
+    return goq_launch_quantize((hipStream_t)stream, bw, out, in, w, codes, pattern, signs, c1, c2);
+}
+
 int goq_pack(void *stream, int bw, int64_t out, int64_t in, const uint8_t *codes, const uint8_t *pattern,
              const uint8_t *signs, const uint16_t *c1, const uint16_t *c2, void *packed)
 {
