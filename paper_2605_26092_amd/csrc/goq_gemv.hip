@@ -15,11 +15,12 @@
 //       weights k = 32 q .. 32 q + 31 of output row 16 j + c of the row block (j = 0..3: four
 //       instructions per basis cover the 64 rows of a row block times one macro-block).  That is
 //       exactly the 16-byte quad (chunk q, row 16 j + c) of the packed layout.
-//   A operand (activations): row i = digit i of the macro-block's 128 activations (rows 8..15
-//       are zero).  Activations are handed over as block fixed point, see stage_run.
-//   D[i][c] = sum_k digit_i(x_k) b[row c][k]: lane (c, q) receives digits 4q .. 4q + 3, so the
-//       slab dot product of a row is spread over two lanes and is put together once, when the
-//       row is stored.
+//   A operand (activations): eight of the 16 rows hold the eight digits of the macro-block's
+//       128 activations (digit d in row 4 (d / 2) + d % 2, the other rows are zero).
+//       Activations are handed over as block fixed point, see stage_run.
+//   D[row][c] = sum_k digit(x_k) b[row c][k]: lane (c, q) receives rows 4q .. 4q + 3, i.e. two
+//       digit sums, so the slab dot product of a row is spread over four lanes and is put
+//       together once, when the row is stored.
 //
 // Work decomposition.  The unit of work is (row group, macro-block g): a ROW GROUP is 8 row
 // blocks of 64 output channels, one row block per wavefront of a 512-thread workgroup.  All units
@@ -47,9 +48,14 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int WAVES = 8;                 // wavefronts (= row blocks) per workgroup
+#ifndef GOQ_WAVES
+#define GOQ_WAVES 8
+#define GOQ_WGS 512
+#define GOQ_WPE 4
+#endif
+constexpr int WAVES = GOQ_WAVES;                 // wavefronts (= row blocks) per workgroup
 constexpr int NT = WAVES * 64;           // threads per workgroup
-constexpr int MAX_WG = 512;              // workgroups per launch (two per CU)
+constexpr int MAX_WG = GOQ_WGS;              // workgroups per launch (two per CU)
 constexpr int SW = 16;                   // units whose activation digits are resident in LDS
 constexpr int XG = 1024;                 // bytes of digits per macro-block: 4 k-groups x 8 digits x 32
 constexpr int XZ = 256;                  // zero bytes in front of the digit table
@@ -272,15 +278,30 @@ __device__ __forceinline__ void stage_window(const GemvArgs &a, int u0, int ns, 
 }
 
 // ---- one unit of one wavefront: 64 rows x one macro-block (H2..H5) --------------------------
-// buf: the lane's quads; vt: exchange table; A, sa: the macro-block's digits (this lane's A row
-// and k-group) and their block scale; cwx: this wavefront's 128-byte exchange area for
+// buf: the lane's quads; vt: LDS address of this lane's copy of the exchange table; A, sa: the macro-block's digits (this lane's A row
+// and k-group) and their block scale; cwx: this wavefront's 256-byte exchange area for
 // coefficient bytes; acc[j]: running sum of row 16 j + c over the digits this lane receives.
 template <int BW>
-__device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, const unsigned char *vt, const v8i &A, int sa,
+__device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, uint32_t vt, const v8i &A, int sa,
                                              unsigned char *cwx, int lane, float (&acc)[4])
 {
     const int c = lane & 15, q = lane >> 4;
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    // The coefficient word of row 16 j + c: bw = 3 spreads it over the row's 16 dwords (two bits
+    // each), so the four lanes (c, 0..3) each hold one byte of it; they swap bytes through LDS,
+    // for all four sub-steps at once.  (LDS operations of one wavefront execute in order; the
+    // empty asm only keeps the compiler from moving the reads above the writes.)
+    if constexpr (BW == 3) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t cw = buf.q[j].x >> 30;
+            cw = __builtin_amdgcn_alignbit(cw, buf.q[j].y, 30);
+            cw = __builtin_amdgcn_alignbit(cw, buf.q[j].z, 30);
+            cw = __builtin_amdgcn_alignbit(cw, buf.q[j].w, 30);
+            cwx[j * 64 + c * 4 + 3 - q] = (unsigned char)cw;
+        }
+        asm volatile("" ::: "memory");
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t dw[4] = {buf.q[j].x, buf.q[j].y, buf.q[j].z, buf.q[j].w};
@@ -290,22 +311,21 @@ __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, const unsig
             msq = buf.ms[j] >> (16 * (q & 1));               // their sign nibbles
         }
         v8i B1, B2;
-        uint32_t cw = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t w = dw[k];
             uint32_t lo, hi;
             goq_decode_bytes<BW, 0>(w, lo, hi);                          // H2: code -> E5M2 byte
-            uint32_t eo;                                                 // 64 * (pattern | signs << 2)
+            uint32_t eo;                       // LDS address of the entry: vt + 64 * (pattern | signs << 2)
             if constexpr (BW == 3) {
                 // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
                 // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
-                eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, 0u, false);
-                cw = __builtin_amdgcn_alignbit(cw, w, 30);               // 2 coefficient bits per dword
+                eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, vt, false);
             } else {
-                eo = (((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 6;
+                eo = vt + ((((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 6);
             }
-            const uint4 e = *reinterpret_cast<const uint4 *>(vt + eo);
+            const u32x4 ev = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
+            const uint4 e = make_uint4(ev.x, ev.y, ev.z, ev.w);
             B1[2 * k] = (int)lo;
             B1[2 * k + 1] = (int)hi;
             B2[2 * k] = (int)(goq_perm(hi, lo, e.x) ^ e.z);               // H4: exchange + sign XOR
@@ -315,22 +335,12 @@ __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, const unsig
         // side, 2^0 on the weight side
         const v4f D1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B1, zero, 1, 1, 0, sa, 0, 127);
         const v4f D2 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B2, zero, 1, 1, 0, sa, 0, 127);
-        // the coefficient word of row 16 j + c: bw = 3 spreads it over the row's 16 dwords, so the
-        // four lanes (c, 0..3) each hold one byte of it; they swap bytes through LDS
         uint32_t cword;
-        if constexpr (BW == 3) {
-            // (LDS operations of one wavefront execute in order; the empty asm only keeps the
-            // compiler from moving the read above the write)
-            unsigned char *slot = cwx + (j & 1) * 64 + c * 4;
-            slot[3 - q] = (unsigned char)cw;
-            asm volatile("" ::: "memory");
-            cword = *reinterpret_cast<const uint32_t *>(slot);
-        } else {
-            cword = buf.mc[j];
-        }
+        if constexpr (BW == 3) cword = *reinterpret_cast<const uint32_t *>(cwx + j * 64 + c * 4);
+        else cword = buf.mc[j];
         // H5: coefficient rescale, once per slab, outside the dot-product loop
-        const float P1 = (D1[0] + D1[1]) + (D1[2] + D1[3]);
-        const float P2 = (D2[0] + D2[1]) + (D2[2] + D2[3]);
+        const float P1 = D1[0] + D1[1];                    // this lane group's two digit sums
+        const float P2 = D2[0] + D2[1];
         const float c1 = __half2float(__ushort_as_half((unsigned short)(cword & 0xffffu)));
         const float c2 = __half2float(__ushort_as_half((unsigned short)(cword >> 16)));
         acc[j] = fmaf(c1, P1, acc[j]);
@@ -361,11 +371,13 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
 {
     const GemvProblem &P = a.p[cur.pi];
     const int u0 = P.begin + cur.rg * P.gn, u1 = u0 + P.gn;
-    // lane l takes over row l of the row block: the sum of row 16 j + c sits in lanes c and c + 16
+    // lane l takes over row l of the row block: the sum of row 16 j + c is spread over the four
+    // lanes c, c + 16, c + 32, c + 48 (two digits each)
     float mine = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float t = acc[j] + __shfl_xor(acc[j], 16);
+        float t = acc[j] + __shfl_xor(acc[j], 16);
+        t += __shfl_xor(t, 32);
         const float r = __shfl(t, lane & 15);
         if ((lane >> 4) == j) mine = r;
     }
@@ -415,14 +427,14 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
 }
 
 template <int BW, int ACT>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemv_kernel(GemvArgs a)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ_WPE))) void gemv_kernel(GemvArgs a)
 {
-    // zeros (A rows 8..15), then the digit table of the resident units and its block scales
+    // zeros (the A rows without a digit), then the digit table of the resident units and its block scales
     __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];
     __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];
     // exchange table: entry v at 64 v + 16 r, four copies r (a lane uses copy lane % 4)
     __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];
-    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 128];
+    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -442,13 +454,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     Stream S = stream_of(a, cur.pi);
     load_unit<BW>(S.packed, S.gn, min(cur.rg * WAVES + wave, S.rbn - 1), cur.g, lane, bufA);
 
-    if (tid < 256) *reinterpret_cast<uint4 *>(vtab + tid * 16) = exchange_entry(tid >> 2);
+    for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
     if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
 
-    // A operand of this lane: row = lane % 16 (digit), k-group q = lane / 16
+    // A operand of this lane: row = lane % 16, k-group q = lane / 16.  Digit d sits in row
+    // 4 (d / 2) + d % 2, so that every lane group receives two digit sums (D rows 4q, 4q + 1) and
+    // rows 4q + 2, 4q + 3 are zero.
     const int arow = lane & 15, q = lane >> 4;
-    const uint32_t abase = arow < 8 ? (uint32_t)(XZ + q * 256 + arow * 32) : 0u;
-    const uint32_t amask = arow < 8 ? ~0u : 0u;
+    const bool arow_live = (arow & 3) < 2;
+    const int digit = 2 * (arow >> 2) + (arow & 1);
+    const uint32_t abase = arow_live ? (uint32_t)(XZ + q * 256 + digit * 32) : 0u;
+    const uint32_t amask = arow_live ? ~0u : 0u;
+    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane & 3) * 16;
 
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     int idx = i0;
@@ -477,8 +494,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
         if (live) {
             const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
             const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
-            const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * arow;     // digit i sits 3 i places lower
-            compute_unit<BW>(bcur, vtab + (lane & 3) * 16, A, sa, cwx + wave * 128, lane, acc);
+            const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * digit;    // digit i sits 3 i places lower
+            compute_unit<BW>(bcur, vt_lane, A, sa, cwx + wave * 256, lane, acc);
         }
         if (!MORE || nxt.rg != cur.rg || nxt.pi != cur.pi) {
             if (live) flush<ACT>(a, cur, acc, i0, i1, wave, lane);
