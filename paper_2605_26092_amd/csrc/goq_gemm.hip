@@ -1,27 +1,36 @@
 // goq_gemm: many-token dual-PoT layer output, Y[tokens][out] = X[tokens][in] * W^T (Eq. 4).
 //
 // The contraction is dense (hundreds to thousands of tokens), so it runs on the matrix cores:
-//   A16: v_mfma_f32_16x16x32_f16, operands fp16, fp32 accumulation
-//   A8 : v_mfma_i32_16x16x64_i8,  operands int8, exact int32 accumulation
-// The weight side is the MFMA B operand.  Its register layout -- lane (n = lane % 16,
-// kg = lane / 16) holds 8 (fp16) or 16 (int8) consecutive k of output channel n -- is exactly
-// one (two) 8-weight micro-block(s) of one row, which is the unit the packed layout stores in a
-// dword.  A lane therefore loads its 16-byte quad (4 micro-blocks of its row), decodes each
+//   A16: v_mfma_f32_32x32x16_f16, operands fp16, fp32 accumulation
+//   A8 : v_mfma_i32_32x32x32_i8,  operands int8, exact int32 accumulation
+// The weight side is the MFMA B operand.  Its register layout -- lane (n = lane % 32,
+// kg = lane / 32) holds 8 (fp16) or 16 (int8) consecutive k of output channel n -- is one (two)
+// 8-weight micro-block(s) of one row, which is the unit the packed layout stores in a dword.  A
+// lane loads two 16-byte quads of its row per slab (micro-blocks 8 kg .. 8 kg + 7), decodes a
 // micro-block in registers with the byte LUT (H2), and rebuilds the residual basis b2 of the same
 // micro-block in registers too (H4): a byte permute by i xor s plus sign flips, both looked up by
 // the 6 metadata bits in a 1 KiB LDS table built at kernel start.  No decoded weight ever goes
-// through memory.  The activation tile of the current 128-wide slab is staged in LDS (XOR-swizzled
-// 16-byte pieces against bank conflicts) and read as the MFMA A operand.
+// through memory.  The order of k inside a slab is free as long as both operands agree: k-step t
+// takes micro-block 8 kg + t of lane group kg.  The activation tile of the slab is staged in LDS
+// (XOR-swizzled 16-byte pieces against bank conflicts) and read as the MFMA A operand.
 //
-// Tiling: workgroup = 4 wavefronts, tile 64 tokens x 128 outputs; each wavefront owns
-// 64 tokens x 32 outputs = 4 x 2 MFMA tiles, with three accumulator sets: the slab partials
-// P1, P2 (restarted every slab by feeding C = 0 to the slab's first MFMA) and the output Y.
-// That fits two wavefronts per SIMD, which measured faster than a 128-token tile at one.
-// The next slab's weights (registers) and activations (global_load_lds straight into the other
-// LDS buffer) are requested before the current slab's MFMAs; one barrier per slab.
+// Tiling: workgroup = 4 wavefronts, tile 64 tokens x 128 outputs; each wavefront owns 64 tokens x
+// 32 outputs = two MFMA tiles of 32 x 32, with three accumulator sets: the slab partials P1, P2
+// (restarted every slab by feeding C = 0 to the slab's first MFMA) and the output Y.  That fits
+// three wavefronts per SIMD.  Measured on this chip with a probe of the same instruction mix:
+// vector-ALU instructions hide only to a small extent behind matrix instructions, whatever the
+// program order (about five per 32x32x16 instruction; every further one costs nearly its full
+// four cycles), so the rate is set by vector-ALU and LDS instructions per matrix instruction.
+// The 32x32x16 instruction halves both per flop compared with 16x16x32 at the same tile.  A
+// 128-token tile (one wavefront per SIMD) spreads the decode over more matrix instructions but
+// needs the partials in accumulator registers, which the rescale can only read through copies:
+// it measured slower.
+// Pipeline: activations of slab g + 2 are requested (global_load_lds, straight into one of three
+// LDS buffers) and the weights of slab g + 1 (registers) at the start of slab g; inside a slab
+// every k-step's MFMAs run on operands prepared during the previous k-step; one barrier per slab.
 // Coefficient rescale (H5) once per slab: Y += c1[n,g] * P1 + c2[n,g] * P2 in fp32, after the
-// slab's MFMAs; a lane needs one (c1, c2) pair per MFMA tile column because every accumulator
-// register of a lane belongs to the same output channel.
+// slab's MFMAs; a lane needs one (c1, c2) pair because every accumulator register of a lane
+// belongs to the same output channel.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <type_traits>
@@ -32,8 +41,9 @@
 namespace {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 #ifndef GOQ_GEMM_TM
 #define GOQ_GEMM_TM 64
@@ -41,8 +51,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int TM = GOQ_GEMM_TM;   // tokens per workgroup tile
 constexpr int TN = 128;       // outputs per workgroup tile
 constexpr int WN = 32;        // outputs per wavefront
-constexpr int MS = TM / 16;   // MFMA tiles along tokens per wavefront
-constexpr int NS = WN / 16;   // MFMA tiles along outputs per wavefront
+constexpr int MS = TM / 32;   // MFMA tiles along tokens per wavefront
 
 struct GemmArgs {
     const uint32_t *packed;
@@ -125,27 +134,28 @@ __device__ __forceinline__ f16x8 widen8(uint32_t lo, uint32_t hi)
     return __builtin_bit_cast(f16x8, v);
 }
 
-template <int BW, int ACT, bool PART>
 #ifndef GOQ_GEMM_MINWAVES
 #define GOQ_GEMM_MINWAVES 2
 #endif
+template <int BW, int ACT, bool PART>
 __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a)
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
     constexpr int XB = (ACT == 0) ? 2 : 1;             // bytes per activation
     constexpr int ROWB = GOQ_N * XB;                   // LDS row stride (XOR-swizzled, not padded)
-    constexpr int KSTEPS = (ACT == 0) ? 4 : 2;         // MFMA k-steps per slab
-    using AccT = typename std::conditional<ACT == 0, f32x4, i32x4>::type;
+    constexpr int KSTEPS = (ACT == 0) ? 8 : 4;         // MFMA k-steps per slab (16 / 32 k each)
+    constexpr int NBUF = 3;                            // activation slabs resident in LDS
+    using AccT = typename std::conditional<ACT == 0, f32x16, i32x16>::type;
+    using OpT = typename std::conditional<ACT == 0, f16x8, i32x4>::type;     // one MFMA operand
 
-    __shared__ __attribute__((aligned(16))) unsigned char xs0[TM * ROWB];
-    __shared__ __attribute__((aligned(16))) unsigned char xs1[TM * ROWB];
+    __shared__ __attribute__((aligned(16))) unsigned char xsb[NBUF][TM * ROWB];
     __shared__ __attribute__((aligned(16))) unsigned char xtab[64 * 16];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int ln = lane & 15;     // MFMA column (output channel) / A row (token)
-    const int lh = lane >> 4;     // k-group
+    const int ln = lane & 31;     // MFMA column (output channel) / A row (token)
+    const int kg = lane >> 5;     // k-group
 
     const int mtiles = (a.tokens + TM - 1) / TM;
     const int mt = blockIdx.x % mtiles;
@@ -155,49 +165,50 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
 
     if (tid < 64) *reinterpret_cast<uint4 *>(xtab + tid * 16) = exchange_entry<ACT>(tid);
 
-    f32x4 Yacc[MS][NS];
+    f32x16 Yacc[MS];
 #pragma unroll
     for (int i = 0; i < MS; ++i)
 #pragma unroll
-        for (int j = 0; j < NS; ++j) Yacc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int v = 0; v < 16; ++v) Yacc[i][v] = 0.f;
 
-    // the quad this lane reads for MFMA column tile j: row n0 + 16 j + ln, chunk lh
-    bool live[NS];
-    const uint32_t *wq[NS];
-#pragma unroll
-    for (int j = 0; j < NS; ++j) {
-        const int row = n0 + 16 * j + ln;
-        live[j] = (row / GOQ_ROWS) < a.rbn;
-        wq[j] = a.packed + goq_quad_index(CH, a.gn, row / GOQ_ROWS, 0, lh, row % GOQ_ROWS);
-    }
+    // the two quads this lane reads per slab: row n0 + ln, chunks 2 kg and 2 kg + 1 (micro-blocks
+    // 8 kg .. 8 kg + 7).  Rows past the last row block are redirected to the last one (their
+    // outputs are never stored), so that every lane always issues the same loads.
+    int wrow = n0 + ln;
+    wrow = (wrow / GOQ_ROWS) < a.rbn ? wrow : a.rbn * GOQ_ROWS - 1;
+    const uint32_t *wq = a.packed + goq_quad_index(CH, a.gn, wrow / GOQ_ROWS, 0, 2 * kg, wrow % GOQ_ROWS);
     const int64_t gstride = (int64_t)CH * GOQ_ROWS * 4;     // dwords between macro-blocks
 
-    // 16-byte pieces of the activation slab this thread moves from HBM to LDS
+    struct Weights {
+        uint4 q0, q1;     // micro-blocks 8 kg .. 8 kg + 3 and 8 kg + 4 .. 8 kg + 7
+        uint4 meta;       // bw = 4: patterns and sign nibbles of these micro-blocks, coefficient word
+    };
+    auto load_weights = [&](int g, Weights &w) {
+        const uint32_t *p = wq + g * gstride;
+        w.q0 = *reinterpret_cast<const uint4 *>(p);
+        w.q1 = *reinterpret_cast<const uint4 *>(p + GOQ_ROWS * 4);
+        w.meta = make_uint4(0, 0, 0, 0);
+        if constexpr (BW == 4) {
+            // chunk 4 of the same row: patterns, signs of m = 0..7, signs of m = 8..15, coefficient word
+            const uint4 mq = *reinterpret_cast<const uint4 *>(p + (4 - 2 * kg) * GOQ_ROWS * 4);
+            w.meta = make_uint4(mq.x >> (16 * kg), kg ? mq.z : mq.y, 0, mq.w);
+        }
+    };
+    auto word_of = [](const Weights &w, int t) {
+        return t == 0 ? w.q0.x : t == 1 ? w.q0.y : t == 2 ? w.q0.z : t == 3 ? w.q0.w
+             : t == 4 ? w.q1.x : t == 5 ? w.q1.y : t == 6 ? w.q1.z : w.q1.w;
+    };
+
+    // Activation slab -> LDS without passing through registers (global_load_lds_dwordx4): each
+    // instruction fills 64 consecutive 16-byte LDS slots, one per lane, from per-lane addresses.
+    // Slot (row, cs) holds k-piece cs ^ f(row): the XOR swizzle makes the 16 rows a quarter of an
+    // MFMA A operand read touches fall into 16 different bank groups (row stride 256 / 128 bytes).
+    // The per-thread byte offsets (inside the token tile) of the pieces a thread requests are
+    // constant over the slabs: a slab's request is one uniform base plus these 32-bit offsets.
     constexpr int PIECES = TM * GOQ_N * XB / 16;
     constexpr int PER_ROW = GOQ_N * XB / 16;
     constexpr int NP = PIECES / 256;
     auto swz = [](int row) { return (ACT == 0) ? (row & 15) : ((row >> 1) & 7); };
-    auto load_weights = [&](int g, uint4 (&wd)[NS], uint4 (&meta)[NS]) {
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            wd[j] = make_uint4(0, 0, 0, 0);
-            meta[j] = make_uint4(0, 0, 0, 0);
-            if (live[j]) {
-                wd[j] = *reinterpret_cast<const uint4 *>(wq[j] + g * gstride);
-                if constexpr (BW == 4) {
-                    // chunk 4 of the same row: patterns, signs lo, signs hi, coefficient word
-                    const uint4 mq = *reinterpret_cast<const uint4 *>(wq[j] + g * gstride + (4 - lh) * GOQ_ROWS * 4);
-                    meta[j] = make_uint4(mq.x >> (8 * lh), (lh < 2 ? mq.y : mq.z) >> (16 * (lh & 1)), 0, mq.w);
-                }
-            }
-        }
-    };
-    // Activation slab -> LDS without passing through registers (global_load_lds_dwordx4): each
-    // instruction fills 64 consecutive 16-byte LDS slots, one per lane, from per-lane addresses.
-    // Slot (row, cs) holds k-piece cs ^ f(row): the XOR swizzle makes the 16 rows an MFMA A
-    // operand read touches fall into 16 different bank groups (row stride is 256 / 128 bytes).
-    // per-thread byte offsets (inside the token tile) of the pieces this thread requests: constant
-    // over the slabs, so a slab's request is one uniform base plus these 32-bit offsets
     uint32_t xoff[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
@@ -209,149 +220,148 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
         xoff[i] = (uint32_t)(m - m0) * (uint32_t)a.in * XB + c * 16;
     }
     const unsigned char *xtile = reinterpret_cast<const unsigned char *>(a.X) + (int64_t)m0 * a.in * XB;
-    auto stage_x = [&](int g, unsigned char *buf) {
+    auto stage_x = [&](int g) {          // exactly NP vector-memory instructions
         const unsigned char *base = xtile + (int64_t)g * GOQ_N * XB;
+        unsigned char *buf = xsb[g % NBUF];
 #pragma unroll
         for (int i = 0; i < NP; ++i)
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void *)(base + xoff[i]),
                 (__attribute__((address_space(3))) void *)(buf + (i * 256 + wave * 64) * 16), 16, 0, 0);
     };
+    // decoded B operands (b1 and b2) of k-step t of a slab (H2, H4)
+    auto decode_step = [&](const Weights &w, int t, OpT &B1, OpT &B2) {
+        if constexpr (ACT == 0) {
+            uint32_t l1, h1, l2, h2;
+            decode_pair<BW, ACT>(word_of(w, t), w.meta, t, xtab, l1, h1, l2, h2);
+            B1 = widen8(l1, h1);
+            B2 = widen8(l2, h2);
+        } else {
+            uint32_t l1, h1, l2, h2, l3, h3, l4, h4;
+            decode_pair<BW, ACT>(word_of(w, 2 * t), w.meta, 2 * t, xtab, l1, h1, l2, h2);
+            decode_pair<BW, ACT>(word_of(w, 2 * t + 1), w.meta, 2 * t + 1, xtab, l3, h3, l4, h4);
+            B1 = i32x4{(int)l1, (int)h1, (int)l3, (int)h3};
+            B2 = i32x4{(int)l2, (int)h2, (int)l4, (int)h4};
+        }
+    };
+    // A operands of k-step t: token 32 i + ln, the 16-byte piece that holds the k of micro-block(s)
+    // 8 kg + MPK t .. of the slab
+    auto read_a = [&](const unsigned char *xs, int t, OpT (&A)[MS]) {
+        const int piece = KSTEPS * kg + t;
+#pragma unroll
+        for (int i = 0; i < MS; ++i)
+            A[i] = *reinterpret_cast<const OpT *>(xs + (32 * i + ln) * ROWB + ((piece ^ swz(32 * i + ln)) * 16));
+    };
+    // coefficient pair of this lane's output channel
+    auto coefficients = [&](const Weights &w, float &c1, float &c2) {
+        uint32_t cw;
+        if constexpr (BW == 3) {
+            // a lane's 8 dwords carry 16 of the 32 bits (lane group 0: c2, lane group 1: c1)
+            uint32_t part = 0;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) part = (part << 2) | (word_of(w, t) >> 30);
+            const uint32_t other = __shfl_xor(part, 32);
+            cw = kg ? (part | (other << 16)) : (other | (part << 16));
+        } else {
+            cw = w.meta.w;
+        }
+        c1 = __half2float(__ushort_as_half((unsigned short)(cw & 0xffffu)));
+        c2 = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
+    };
 
-    // slab 0 is staged up front; afterwards the next slab's weights and activations are requested
-    // from HBM before the current slab's MFMAs (activations land in the other LDS buffer)
-    uint4 wd[NS], meta[NS], wdn[NS], metan[NS];
-    load_weights(0, wd, meta);
-    stage_x(0, xs0);
+    // Prologue: slabs 0 and 1 are requested and waited for.
+    Weights wd, wn;
+    load_weights(0, wd);
+    stage_x(0);
+    if (a.gn > 1) stage_x(1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
+    OpT B1, B2, A[MS];
+    decode_step(wd, 0, B1, B2);
+    read_a(xsb[0], 0, A);
+
     for (int g = 0; g < a.gn; ++g) {
-        const unsigned char *xs = (g & 1) ? xs1 : xs0;
-        if (g + 1 < a.gn) {
-            load_weights(g + 1, wdn, metan);
-            stage_x(g + 1, (g & 1) ? xs0 : xs1);
-        }
+        const unsigned char *xs = xsb[g % NBUF];
+        const bool more2 = g + 2 < a.gn;
+        // (the weight request is unconditional, on a clamped slab index: past the last slab the
+        // result is not used; the activation request comes last so that the wait below is exact)
+        load_weights(min(g + 1, a.gn - 1), wn);
+        if (more2) stage_x(g + 2);
 
-        // ---- coefficient pair of this lane's column in every column tile
-        float c1[NS], c2[NS];
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            uint32_t cw;
-            if constexpr (BW == 3) {
-                // this lane's 4 dwords carry 8 of the 32 bits; the 4 k-group lanes of a column
-                // (lane, lane^16, lane^32, lane^48) carry the rest
-                uint32_t part = ((wd[j].x >> 30) << 6) | ((wd[j].y >> 30) << 4) | ((wd[j].z >> 30) << 2) | (wd[j].w >> 30);
-                part <<= (24 - 8 * lh);
-                part |= __shfl_xor(part, 16);
-                part |= __shfl_xor(part, 32);
-                cw = part;
-            } else {
-                cw = meta[j].w;
-            }
-            c1[j] = __half2float(__ushort_as_half((unsigned short)(cw & 0xffffu)));
-            c2[j] = __half2float(__ushort_as_half((unsigned short)(cw >> 16)));
-        }
+        float c1, c2;
+        coefficients(wd, c1, c2);
 
-        // ---- the slab's MFMAs: every A operand read from LDS feeds the b1 and b2 MFMAs of both
-        //      column tiles
-        AccT P1[MS][NS], P2[MS][NS];
+        AccT P1[MS], P2[MS];
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            if constexpr (ACT == 0) {
-                f16x8 B1[NS], B2[NS];
+        for (int t = 0; t < KSTEPS; ++t) {
+            const OpT B1c = B1, B2c = B2;
+            OpT Ac[MS];
 #pragma unroll
-                for (int j = 0; j < NS; ++j) {
-                    const uint32_t w = ks == 0 ? wd[j].x : ks == 1 ? wd[j].y : ks == 2 ? wd[j].z : wd[j].w;
-                    uint32_t l1, h1, l2, h2;
-                    decode_pair<BW, ACT>(w, meta[j], ks, xtab, l1, h1, l2, h2);
-                    B1[j] = widen8(l1, h1);
-                    B2[j] = widen8(l2, h2);
-                }
-#pragma unroll
-                for (int i = 0; i < MS; ++i) {
-                    // A operand: token 16 i + ln, k = 8 (4 lh + ks) .. + 7 of the slab
-                    const f16x8 A = *reinterpret_cast<const f16x8 *>(xs + (16 * i + ln) * ROWB + (((4 * lh + ks) ^ swz(16 * i + ln)) * 16));
-                    const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int j = 0; j < NS; ++j) {
-                        P1[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B1[j], ks == 0 ? z : P1[i][j], 0, 0, 0);
-                        P2[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B2[j], ks == 0 ? z : P2[i][j], 0, 0, 0);
-                    }
-                }
+            for (int i = 0; i < MS; ++i) Ac[i] = A[i];
+            if (t + 1 < KSTEPS) {
+                decode_step(wd, t + 1, B1, B2);
+                read_a(xs, t + 1, A);
             } else {
-                i32x4 B1[NS], B2[NS];
+                // last k-step of the slab.  Everything older than this slab's activation request
+                // has landed once at most NP vector-memory operations are outstanding (they return
+                // in order): slab g + 1's activations, requested a slab ago, and its weights.
+                if (more2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NP) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                decode_step(wn, 0, B1, B2);
+                read_a(xsb[min(g + 1, a.gn - 1) % NBUF], 0, A);
+            }
 #pragma unroll
-                for (int j = 0; j < NS; ++j) {
-                    const uint32_t wa = ks == 0 ? wd[j].x : wd[j].z;
-                    const uint32_t wb = ks == 0 ? wd[j].y : wd[j].w;
-                    uint32_t l1, h1, l2, h2, l3, h3, l4, h4;
-                    decode_pair<BW, ACT>(wa, meta[j], 2 * ks, xtab, l1, h1, l2, h2);
-                    decode_pair<BW, ACT>(wb, meta[j], 2 * ks + 1, xtab, l3, h3, l4, h4);
-                    B1[j] = i32x4{(int)l1, (int)h1, (int)l3, (int)h3};
-                    B2[j] = i32x4{(int)l2, (int)h2, (int)l4, (int)h4};
-                }
+            for (int i = 0; i < MS; ++i) {
+                AccT z;
 #pragma unroll
-                for (int i = 0; i < MS; ++i) {
-                    // A operand: token 16 i + ln, k = 32 lh + 16 ks .. + 15 of the slab
-                    const i32x4 A = *reinterpret_cast<const i32x4 *>(xs + (16 * i + ln) * ROWB + (((2 * lh + ks) ^ swz(16 * i + ln)) * 16));
-                    const i32x4 z = i32x4{0, 0, 0, 0};
-#pragma unroll
-                    for (int j = 0; j < NS; ++j) {
-                        P1[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B1[j], ks == 0 ? z : P1[i][j], 0, 0, 0);
-                        P2[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B2[j], ks == 0 ? z : P2[i][j], 0, 0, 0);
-                    }
+                for (int v = 0; v < 16; ++v) z[v] = 0;
+                if constexpr (ACT == 0) {
+                    P1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B1c, t == 0 ? z : P1[i], 0, 0, 0);
+                    P2[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B2c, t == 0 ? z : P2[i], 0, 0, 0);
+                } else {
+                    P1[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ac[i], B1c, t == 0 ? z : P1[i], 0, 0, 0);
+                    P2[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ac[i], B2c, t == 0 ? z : P2[i], 0, 0, 0);
                 }
             }
-#ifdef GOQ_GEMM_SCHEDBAR
-            __builtin_amdgcn_sched_barrier(0);
-#endif
         }
-        // ---- coefficient rescale, once per slab, outside the dot-product loop (H5)
+        // ---- coefficient rescale, once per slab, outside the dot-product loop (H5).  Register v
+        //      of a 32 x 32 tile: token 8 (v / 4) + 4 kg + v % 4, output ln.
 #pragma unroll
-        for (int i = 0; i < MS; ++i)
+        for (int i = 0; i < MS; ++i) {
 #pragma unroll
-            for (int j = 0; j < NS; ++j) {
+            for (int v = 0; v < 16; ++v) {
+                Yacc[i][v] = fmaf(c1, (float)P1[i][v], Yacc[i][v]);
+                Yacc[i][v] = fmaf(c2, (float)P2[i][v], Yacc[i][v]);
+            }
+            if constexpr (PART) {
+                // exact int32 slab partials [tokens][out][in/128][2] (verification output)
+                const int n = n0 + ln;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    Yacc[i][j][v] = fmaf(c1[j], (float)P1[i][j][v], Yacc[i][j][v]);
-                    Yacc[i][j][v] = fmaf(c2[j], (float)P2[i][j][v], Yacc[i][j][v]);
-                }
-                if constexpr (PART) {
-                    // exact int32 slab partials [tokens][out][in/128][2] (verification output)
-                    const int n = n0 + 16 * j + ln;
-                    int32_t *pp = a.partials + (((int64_t)(m0 + 16 * i + 4 * lh) * a.out + n) * a.gn + g) * 2;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int m = m0 + 16 * i + 4 * lh + v;
-                        if (m < a.tokens && n < a.out)
-                            *reinterpret_cast<int2 *>(pp + (int64_t)v * a.out * a.gn * 2) = make_int2(P1[i][j][v], P2[i][j][v]);
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + 32 * i + 8 * (v / 4) + 4 * kg + (v % 4);
+                    if (m < a.tokens && n < a.out)
+                        *reinterpret_cast<int2 *>(a.partials + (((int64_t)m * a.out + n) * a.gn + g) * 2) =
+                            make_int2(P1[i][v], P2[i][v]);
                 }
             }
-        if (g + 1 < a.gn) {
-#pragma unroll
-            for (int j = 0; j < NS; ++j) { wd[j] = wdn[j]; meta[j] = metan[j]; }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next slab's activations are in LDS
-        __syncthreads();
+        wd = wn;
     }
 
-    // ---- store the tile (H6): lane holds Y[m0 + 16 i + 4 lh + v][n0 + 16 j + ln]
+    // ---- store the tile (H6)
+    const int n = n0 + ln;
 #pragma unroll
     for (int i = 0; i < MS; ++i)
 #pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            const int n = n0 + 16 * j + ln;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int m = m0 + 16 * i + 4 * lh + v;
-                if (m >= a.tokens || n >= a.out) continue;
-                float y = Yacc[i][j][v];
-                if constexpr (ACT == 1) y *= a.sx[m] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
-                if (a.ytype == GOQ_F32) reinterpret_cast<float *>(a.Y)[(int64_t)m * a.out + n] = y;
-                else reinterpret_cast<__half *>(a.Y)[(int64_t)m * a.out + n] = __float2half(y);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int m = m0 + 32 * i + 8 * (v / 4) + 4 * kg + (v % 4);
+            if (m >= a.tokens || n >= a.out) continue;
+            float y = Yacc[i][v];
+            if constexpr (ACT == 1) y *= a.sx[m] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
+            if (a.ytype == GOQ_F32) reinterpret_cast<float *>(a.Y)[(int64_t)m * a.out + n] = y;
+            else reinterpret_cast<__half *>(a.Y)[(int64_t)m * a.out + n] = __float2half(y);
         }
 }
 
