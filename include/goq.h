@@ -88,7 +88,7 @@ int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed
 
 /* Batch-1 layer output (Eq. 4 with one token).
  *   act = GOQ_A16: x is fp16 [in], sx must be NULL.
- *   act = GOQ_A8 : x is int8 [in], sx points to one fp32 scale (device).
+ *   act = GOQ_A8 : x is int8 [in], sx points to one fp32 scale (device).  Both bit widths.
  *   y is [out] of ytype.  The PoT codes are decoded to 8-bit floats (a power of two is exact in
  *   E5M2) and b2 is rebuilt from b1 by a byte permute and a sign flip; the two slab dot products
  *   run on the 8-bit-float matrix instruction against x written as block fixed point (24 bits
@@ -116,8 +116,11 @@ int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *de
 /* Many-token layer output (Eq. 4), Y[tokens][out] = X[tokens][in] * W^T.
  *   act = GOQ_A16: X fp16, sx NULL; PoT codes are decoded to fp16 operands of the fp16 MFMA,
  *                  fp32 accumulation.
- *   act = GOQ_A8 : X int8, sx fp32 [tokens]; PoT codes are decoded to int8 (b * 2^(E-1)) operands
- *                  of the int8 MFMA, exact int32 slab partials.
+ *   act = GOQ_A8 : X int8, sx fp32 [tokens].  bw = 3: PoT codes are decoded to int8 (b * 2^(E-1))
+ *                  operands of the int8 MFMA, exact int32 slab partials.  bw = 4: b * 2^7 reaches
+ *                  +128, which is no int8; the int8 activations are widened to fp16 on their way
+ *                  into LDS and the fp16 MFMA is used -- every product is exact and a slab sum
+ *                  needs at most 22 bits, so the fp32 accumulators hold the same exact integers.
  *   partials (optional, GOQ_A8 only, else NULL): int32 [tokens][out][in/128][2] receives the
  *   exact slab partials P_1, P_2 (in units of 2^-(E-1)). */
 int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t in,

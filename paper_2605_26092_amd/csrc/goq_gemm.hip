@@ -2,7 +2,11 @@
 //
 // The contraction is dense (hundreds to thousands of tokens), so it runs on the matrix cores:
 //   A16: v_mfma_f32_32x32x16_f16, operands fp16, fp32 accumulation
-//   A8 : v_mfma_i32_32x32x32_i8,  operands int8, exact int32 accumulation
+//   A8 : v_mfma_i32_32x32x32_i8,  operands int8, exact int32 accumulation (bw = 3)
+//   A8 with bw = 4: b * 2^7 reaches +128, which is no int8.  The int8 activations are widened to
+//        fp16 on their way into LDS and the fp16 instruction is used: int8 values and powers of
+//        two down to 2^-7 are exact in fp16, every product is exact, and a slab sum needs at most
+//        22 bits, so the fp32 accumulators hold the exact integers (in units of 2^-7).
 // The weight side is the MFMA B operand.  Its register layout -- lane (n = lane % 32,
 // kg = lane / 32) holds 8 (fp16) or 16 (int8) consecutive k of output channel n -- is one (two)
 // 8-weight micro-block(s) of one row, which is the unit the packed layout stores in a dword.  A
@@ -141,12 +145,14 @@ template <int BW, int ACT, bool PART>
 __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a)
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
-    constexpr int XB = (ACT == 0) ? 2 : 1;             // bytes per activation
+    constexpr bool F16 = (ACT != 1);                   // fp16 MFMA (ACT 0: fp16 x; ACT 2: int8 x widened)
+    constexpr int WACT = F16 ? 0 : 1;                  // how the weights are decoded
+    constexpr int XB = F16 ? 2 : 1;                    // bytes per activation in LDS
     constexpr int ROWB = GOQ_N * XB;                   // LDS row stride (XOR-swizzled, not padded)
-    constexpr int KSTEPS = (ACT == 0) ? 8 : 4;         // MFMA k-steps per slab (16 / 32 k each)
+    constexpr int KSTEPS = F16 ? 8 : 4;                // MFMA k-steps per slab (16 / 32 k each)
     constexpr int NBUF = 3;                            // activation slabs resident in LDS
-    using AccT = typename std::conditional<ACT == 0, f32x16, i32x16>::type;
-    using OpT = typename std::conditional<ACT == 0, f16x8, i32x4>::type;     // one MFMA operand
+    using AccT = typename std::conditional<F16, f32x16, i32x16>::type;
+    using OpT = typename std::conditional<F16, f16x8, i32x4>::type;          // one MFMA operand
 
     __shared__ __attribute__((aligned(16))) unsigned char xsb[NBUF][TM * ROWB];
     __shared__ __attribute__((aligned(16))) unsigned char xtab[64 * 16];
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     const int m0 = mt * TM;
     const int n0 = nt * TN + wave * WN;
 
-    if (tid < 64) *reinterpret_cast<uint4 *>(xtab + tid * 16) = exchange_entry<ACT>(tid);
+    if (tid < 64) *reinterpret_cast<uint4 *>(xtab + tid * 16) = exchange_entry<WACT>(tid);
 
     f32x16 Yacc[MS];
 #pragma unroll
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     constexpr int PIECES = TM * GOQ_N * XB / 16;
     constexpr int PER_ROW = GOQ_N * XB / 16;
     constexpr int NP = PIECES / 256;
-    auto swz = [](int row) { return (ACT == 0) ? (row & 15) : ((row >> 1) & 7); };
+    auto swz = [](int row) { return F16 ? (row & 15) : ((row >> 1) & 7); };
     uint32_t xoff[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
@@ -229,16 +235,56 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                 (const __attribute__((address_space(1))) void *)(base + xoff[i]),
                 (__attribute__((address_space(3))) void *)(buf + (i * 256 + wave * 64) * 16), 16, 0, 0);
     };
+    // ACT == 2: the int8 activations pass through registers and are widened to fp16 on their way
+    // into LDS.  A thread moves NPS 16-byte pieces (16 activations each) per slab; piece cs of a
+    // row becomes the fp16 pieces 2 cs and 2 cs + 1.  int8 -> fp16 without a conversion
+    // instruction: 0x6400 | (x + 128) is the fp16 number 1024 + (x + 128); subtracting 1152 leaves x.
+    constexpr int NPS = TM * GOQ_N / 16 / 256;
+    uint32_t soff[NPS];
+#pragma unroll
+    for (int i = 0; i < NPS; ++i) {
+        const int S = i * 256 + tid;
+        int m = m0 + S / 8;
+        m = m < a.tokens ? m : a.tokens - 1;
+        soff[i] = (uint32_t)(m - m0) * (uint32_t)a.in + (S % 8) * 16;
+    }
+    auto fetch_x = [&](int g, uint4 (&r)[NPS]) {
+        const unsigned char *base = reinterpret_cast<const unsigned char *>(a.X) + (int64_t)m0 * a.in + (int64_t)g * GOQ_N;
+#pragma unroll
+        for (int i = 0; i < NPS; ++i) r[i] = *reinterpret_cast<const uint4 *>(base + soff[i]);
+    };
+    auto write_x = [&](int g, const uint4 (&r)[NPS]) {
+        unsigned char *buf = xsb[g % NBUF];
+        const goq_half2 off = {(_Float16)1152.f, (_Float16)1152.f};
+#pragma unroll
+        for (int i = 0; i < NPS; ++i) {
+            const int S = i * 256 + tid;
+            const int row = S / 8, cs = S % 8;
+            const uint32_t d[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+            uint32_t h[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t u = d[k] ^ 0x80808080u;
+                const goq_half2 lo = __builtin_bit_cast(goq_half2, goq_perm(0x64646464u, u, 0x04010400u)) - off;
+                const goq_half2 hi = __builtin_bit_cast(goq_half2, goq_perm(0x64646464u, u, 0x04030402u)) - off;
+                h[2 * k] = __builtin_bit_cast(uint32_t, lo);
+                h[2 * k + 1] = __builtin_bit_cast(uint32_t, hi);
+            }
+            unsigned char *dst = buf + row * ROWB;
+            *reinterpret_cast<uint4 *>(dst + (((2 * cs) ^ swz(row)) * 16)) = make_uint4(h[0], h[1], h[2], h[3]);
+            *reinterpret_cast<uint4 *>(dst + (((2 * cs + 1) ^ swz(row)) * 16)) = make_uint4(h[4], h[5], h[6], h[7]);
+        }
+    };
     // decoded B operands (b1 and b2) of k-step t of a slab (H2, H4)
     auto decode_step = [&](const Weights &w, int t, OpT &B1, OpT &B2) {
-        if constexpr (ACT == 0) {
+        if constexpr (F16) {
             uint32_t l1, h1, l2, h2;
-            decode_pair<BW, ACT>(word_of(w, t), w.meta, t, xtab, l1, h1, l2, h2);
+            decode_pair<BW, WACT>(word_of(w, t), w.meta, t, xtab, l1, h1, l2, h2);
             B1 = widen8(l1, h1);
             B2 = widen8(l2, h2);
         } else {
             uint32_t l1, h1, l2, h2, l3, h3, l4, h4;
-            decode_pair<BW, ACT>(word_of(w, 2 * t), w.meta, 2 * t, xtab, l1, h1, l2, h2);
+            decode_pair<BW, WACT>(word_of(w, 2 * t), w.meta, 2 * t, xtab, l1, h1, l2, h2);
             decode_pair<BW, ACT>(word_of(w, 2 * t + 1), w.meta, 2 * t + 1, xtab, l3, h3, l4, h4);
             B1 = i32x4{(int)l1, (int)h1, (int)l3, (int)h3};
             B2 = i32x4{(int)l2, (int)h2, (int)l4, (int)h4};
@@ -271,9 +317,19 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
 
     // Prologue: slabs 0 and 1 are requested and waited for.
     Weights wd, wn;
+    uint4 xr[NPS];
     load_weights(0, wd);
-    stage_x(0);
-    if (a.gn > 1) stage_x(1);
+    if constexpr (ACT == 2) {
+        fetch_x(0, xr);
+        write_x(0, xr);
+        if (a.gn > 1) {
+            fetch_x(1, xr);
+            write_x(1, xr);
+        }
+    } else {
+        stage_x(0);
+        if (a.gn > 1) stage_x(1);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -287,7 +343,11 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
         // (the weight request is unconditional, on a clamped slab index: past the last slab the
         // result is not used; the activation request comes last so that the wait below is exact)
         load_weights(min(g + 1, a.gn - 1), wn);
-        if (more2) stage_x(g + 2);
+        if constexpr (ACT == 2) {
+            if (more2) fetch_x(g + 2, xr);
+        } else {
+            if (more2) stage_x(g + 2);
+        }
 
         float c1, c2;
         coefficients(wd, c1, c2);
@@ -306,8 +366,14 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                 // last k-step of the slab.  Everything older than this slab's activation request
                 // has landed once at most NP vector-memory operations are outstanding (they return
                 // in order): slab g + 1's activations, requested a slab ago, and its weights.
-                if (more2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NP) : "memory");
-                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if constexpr (ACT == 2) {
+                    // (register path: slab g + 2 is written here; its buffer was last read before
+                    // the previous slab's barrier, and it is first read after the next one)
+                    if (more2) write_x(g + 2, xr);
+                } else {
+                    if (more2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NP) : "memory");
+                    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
                 __syncthreads();
                 decode_step(wn, 0, B1, B2);
                 read_a(xsb[min(g + 1, a.gn - 1) % NBUF], 0, A);
@@ -317,7 +383,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                 AccT z;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) z[v] = 0;
-                if constexpr (ACT == 0) {
+                if constexpr (F16) {
                     P1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B1c, t == 0 ? z : P1[i], 0, 0, 0);
                     P2[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B2c, t == 0 ? z : P2[i], 0, 0, 0);
                 } else {
@@ -343,7 +409,9 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                     const int m = m0 + 32 * i + 8 * (v / 4) + 4 * kg + (v % 4);
                     if (m < a.tokens && n < a.out)
                         *reinterpret_cast<int2 *>(a.partials + (((int64_t)m * a.out + n) * a.gn + g) * 2) =
-                            make_int2(P1[i][v], P2[i][v]);
+                            F16 ? make_int2((int)((float)P1[i][v] * (float)(1 << ((1 << (BW - 1)) - 1))),
+                                            (int)((float)P2[i][v] * (float)(1 << ((1 << (BW - 1)) - 1))))
+                                : make_int2((int)P1[i][v], (int)P2[i][v]);
                 }
             }
         }
@@ -360,6 +428,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
             if (m >= a.tokens || n >= a.out) continue;
             float y = Yacc[i][v];
             if constexpr (ACT == 1) y *= a.sx[m] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
+            if constexpr (ACT == 2) y *= a.sx[m];
             if (a.ytype == GOQ_F32) reinterpret_cast<float *>(a.Y)[(int64_t)m * a.out + n] = y;
             else reinterpret_cast<__half *>(a.Y)[(int64_t)m * a.out + n] = __float2half(y);
         }
@@ -370,8 +439,8 @@ int launch(hipStream_t st, const GemmArgs &a)
 {
     const int mtiles = (a.tokens + TM - 1) / TM;
     const int ntiles = (a.out + TN - 1) / TN;
-    if (ACT == 1 && a.partials)
-        hipLaunchKernelGGL((gemm_kernel<BW, ACT, (ACT == 1)>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
+    if (ACT != 0 && a.partials)
+        hipLaunchKernelGGL((gemm_kernel<BW, ACT, (ACT != 0)>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL((gemm_kernel<BW, ACT, false>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
     return goq_check_launch("goq_gemm");
@@ -398,5 +467,5 @@ int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a);
     if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a);
     if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, a);
-    return goq_set_error(GOQ_EUNSUPPORTED, "goq_gemm: bw=4 with int8 activations is not implemented");
+    return launch<4, 2>(st, a);
 }

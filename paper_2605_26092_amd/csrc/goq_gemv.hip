@@ -542,8 +542,6 @@ Region *scratch_base()
 
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs)
 {
-    if (bw == 4 && act == GOQ_A8)
-        return goq_set_error(GOQ_EUNSUPPORTED, "goq_gemv: bw=4 with int8 activations is not implemented");
     GemvArgs a;
     a.n = n;
     int64_t total = 0;
@@ -577,5 +575,6 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     a.pr = a.total % nwg;
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, nwg);
     if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a, nwg);
+    if (bw == 4 && act == GOQ_A8) return launch<4, 1>(st, a, nwg);
     return launch<4, 0>(st, a, nwg);
 }

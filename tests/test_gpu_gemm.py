@@ -55,12 +55,13 @@ def test_gemm_a16_small(oracle, bw, shape):
             assert e2 <= 2e-6, e2
 
 
+@pytest.mark.parametrize("bw", [3, 4])
 @pytest.mark.parametrize("shape", [(1, 16, 128), (5, 64, 128), (17, 130, 384), (197, 768, 768), (300, 200, 3072)])
-def test_gemm_a8_w3_bit_exact_partials(oracle, shape):
+def test_gemm_a8_bit_exact_partials(oracle, bw, shape):
     import paper_2605_26092_amd as goq
     tokens, out, inn = shape
-    print("gemm a8 tokens=%d out=%d in=%d" % (tokens, out, inn), flush=True)
-    q = _quantize(oracle, 3, out, inn, 42)
+    print("gemm a8 bw=%d tokens=%d out=%d in=%d" % (bw, tokens, out, inn), flush=True)
+    q = _quantize(oracle, bw, out, inn, 42)
     Xq, sx = goq_inputs.activations_a8(tokens, inn, config_id=42, tensor_id=200 + tokens)
     ref, rparts = oracle.gemm_a8(q, Xq, sx, threads=8, want_partials=True)
     Y, parts = _gemm(goq, q, Xq, goq.A8, goq.F32, sx_np=sx, want_partials=True)
@@ -96,6 +97,19 @@ def test_gemm_edge_cases(oracle):
     ref8, rp = oracle.gemm_a8(q, Xq, sx, want_partials=True)
     Y8, parts = _gemm(goq, q, Xq, goq.A8, goq.F32, sx_np=sx, want_partials=True)
     assert np.array_equal(parts.cpu().numpy(), rp)
+    # bw = 4: the +1 state is 128 in units of 2^-7 (no int8); +-127 activations on it and on the
+    # smallest state (-2^-7) give the largest and the smallest slab sums
+    q4 = goq_inputs.canonical_random(4, 70, 256, config_id=44)
+    q4["codes"][:35] = 0                                  # all +1
+    q4["codes"][35:] = 15                                 # all -2^-7
+    ref4, rp4 = oracle.gemm_a8(q4, Xq, sx, want_partials=True)
+    Y4, parts4 = _gemm(goq, q4, Xq, goq.A8, goq.F32, sx_np=sx, want_partials=True)
+    assert np.array_equal(parts4.cpu().numpy(), rp4)
+    Xq[:] = 127                                           # no cancellation: 128 * 127 * 128 per slab
+    ref4, rp4 = oracle.gemm_a8(q4, Xq, sx, want_partials=True)
+    Y4, parts4 = _gemm(goq, q4, Xq, goq.A8, goq.F32, sx_np=sx, want_partials=True)
+    assert np.array_equal(parts4.cpu().numpy(), rp4)
+    assert np.max(np.abs(Y4.cpu().numpy().astype(np.float64) - ref4)) <= 1e-5 * np.max(np.abs(ref4))
 
 
 @pytest.mark.parametrize("bw,name,out,inn", [(3, "q", 4096, 4096), (4, "q", 4096, 4096), (3, "down", 4096, 11008)])

@@ -53,12 +53,13 @@ def test_gemv_a16_small(oracle, bw, ytype_name, shape):
         assert e2 <= 2e-6, e2
 
 
+@pytest.mark.parametrize("bw", [3, 4])
 @pytest.mark.parametrize("shape", [(1, 128), (64, 128), (17, 384), (200, 768), (1100, 1024)])
-def test_gemv_a8_w3(oracle, shape):
+def test_gemv_a8(oracle, bw, shape):
     import paper_2605_26092_amd as goq
     out, inn = shape
-    print("gemv a8 out=%d in=%d" % (out, inn), flush=True)
-    q = _quantize(oracle, 3, out, inn, 32)
+    print("gemv a8 bw=%d out=%d in=%d" % (bw, out, inn), flush=True)
+    q = _quantize(oracle, bw, out, inn, 32)
     xq, sx = goq_inputs.activations_a8(1, inn, config_id=32, tensor_id=200 + out)
     ref, _ = oracle.gemm_a8(q, xq, sx, threads=8)
     y = _run_gemv(goq, q, xq, goq.A8, goq.F32, sx_np=sx)
