@@ -8,6 +8,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgoq.so")
 
+# per-file extras: the GEMV's leading scalar kernel arguments arrive in scalar registers
+EXTRA = {"goq_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=9"]}
+
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
          # packed fp32 VALU forms are kept off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -28,7 +31,8 @@ def build(force: bool = True, extra=()) -> str:
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
     for src in srcs:
         obj = os.path.join(HERE, "_build", os.path.basename(src) + ".o")
-        cmd = ["hipcc", "-c"] + [f for f in FLAGS if f != "-shared"] + list(extra) + ["-o", obj, src]
+        cmd = (["hipcc", "-c"] + [f for f in FLAGS if f != "-shared"] + EXTRA.get(os.path.basename(src), [])
+               + list(extra) + ["-o", obj, src])
         procs.append((src, subprocess.Popen(cmd)))
         objs.append(obj)
     for src, p in procs:

@@ -426,8 +426,14 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
     }
 }
 
+// The leading scalar arguments repeat what the first instructions of a workgroup need -- the piece
+// sizes and the first unit of every problem -- as separate kernel arguments, so that they can be
+// preloaded into scalar registers at wavefront launch (-amdgpu-kernarg-preload-count): finding
+// the workgroup's first unit then costs no memory round trip, and its weights are requested one
+// round trip (the problem's fields) after the wavefront starts.
 template <int BW, int ACT>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ_WPE))) void gemv_kernel(GemvArgs a)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ_WPE)))
+void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, int bg6, int bg7, GemvArgs a)
 {
     // zeros (the A rows without a digit), then the digit table of the resident units and its block scales
     __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];
@@ -441,13 +447,28 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // this workgroup's piece [i0, i1) of the unit sequence
-    const int i0 = __builtin_amdgcn_readfirstlane(piece_begin(a, blockIdx.x));
-    const int i1 = __builtin_amdgcn_readfirstlane(piece_begin(a, blockIdx.x + 1));
+    const int bid = blockIdx.x;
+    const int i0 = __builtin_amdgcn_readfirstlane(bid * pq + min(bid, pr));
+    const int i1 = __builtin_amdgcn_readfirstlane((bid + 1) * pq + min(bid + 1, pr));
     if (i0 >= i1) return;
 
-    Cursor cur = locate(a, i0);
-    cur.rg = __builtin_amdgcn_readfirstlane(cur.rg);
-    cur.g = __builtin_amdgcn_readfirstlane(cur.g);
+    // the problem that holds unit i0, by compares with the (preloaded) first units: unused
+    // problems start at INT_MAX
+    Cursor cur;
+    {
+        const int bg[GOQ_MAX_BATCH] = {0, bg1, bg2, bg3, bg4, bg5, bg6, bg7};
+        int pi = 0, b0 = 0;
+#pragma unroll
+        for (int i = 1; i < GOQ_MAX_BATCH; ++i) {
+            const bool ge = i0 >= bg[i];
+            pi += ge ? 1 : 0;
+            b0 = ge ? bg[i] : b0;
+        }
+        const int gn = a.p[pi].gn;
+        cur.pi = __builtin_amdgcn_readfirstlane(pi);
+        cur.rg = __builtin_amdgcn_readfirstlane((i0 - b0) / gn);
+        cur.g = __builtin_amdgcn_readfirstlane((i0 - b0) % gn);
+    }
 
     // the first unit's weights are requested before anything else
     UnitBuf<BW> bufA, bufB;
@@ -517,7 +538,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ
 template <int BW, int ACT>
 int launch(hipStream_t st, const GemvArgs &a, int nwg)
 {
-    hipLaunchKernelGGL((gemv_kernel<BW, ACT>), dim3(nwg), dim3(NT), 0, st, a);
+    static_assert(GOQ_MAX_BATCH == 8, "the kernel takes the first units of problems 1..7 as arguments");
+    hipLaunchKernelGGL((gemv_kernel<BW, ACT>), dim3(nwg), dim3(NT), 0, st, a.pq, a.pr, a.p[1].begin, a.p[2].begin,
+                       a.p[3].begin, a.p[4].begin, a.p[5].begin, a.p[6].begin, a.p[7].begin, a);
     return goq_check_launch("goq_gemv");
 }
 
