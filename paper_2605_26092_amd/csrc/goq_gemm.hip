@@ -91,44 +91,47 @@ __device__ __forceinline__ uint4 exchange_entry(int v)
     return make_uint4(0x03020100u ^ srep, 0x07060504u ^ srep, mlo, mhi);
 }
 
-// 16 * (pattern | signs << 2) of micro-block q (0..3) of a lane's quad
+// LDS address of the exchange table entry of a micro-block: vt + 16 * (pattern | signs << 2)
 template <int BW>
-__device__ __forceinline__ uint32_t exchange_offset(uint32_t w, const uint4 &meta, int m)
+__device__ __forceinline__ uint32_t exchange_address(uint32_t w, const uint4 &meta, int m, uint32_t vt)
 {
     if constexpr (BW == 3) {
-        const uint32_t t = w & 0x00C0C0C0u;
-        const uint32_t u = __umul24(t, 0x1041u);
-        return (u >> 14) & 0x3F0u;
+        // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) -> contiguous 6-bit index at bits 18..23
+        const uint32_t u = __umul24(w & 0x00C0C0C0u, 0x1041u);
+        return vt + ((u >> 14) & 0x3F0u);
     } else {
         const uint32_t pat = (meta.x >> (2 * m)) & 3u;
         const uint32_t sg = (meta.y >> (4 * (m & 7))) & 15u;   // meta.y already holds this lane's half
-        return (pat | (sg << 2)) << 4;
+        return vt + ((pat | (sg << 2)) << 4);
     }
-}
-
-// per-byte two's complement negation of the bytes selected by mask (0xFF per selected byte)
-__device__ __forceinline__ uint32_t negate_bytes(uint32_t x, uint32_t mask)
-{
-    const uint32_t a = x ^ mask;
-    const uint32_t one = mask & 0x01010101u;
-    return ((a & 0x7F7F7F7Fu) + one) ^ (a & 0x80808080u);
 }
 
 // Decode one micro-block dword into the bytes of b1 and b2 (elements 0..3 in lo, 4..7 in hi).
 template <int BW, int ACT>
-__device__ __forceinline__ void decode_pair(uint32_t w, const uint4 &meta, int m, const unsigned char *xtab,
+__device__ __forceinline__ void decode_pair(uint32_t w, const uint4 &meta, int m, uint32_t vt,
                                             uint32_t &b1lo, uint32_t &b1hi, uint32_t &b2lo, uint32_t &b2hi)
 {
-    goq_decode_bytes<BW, ACT>(w, b1lo, b1hi);
-    const uint4 e = *reinterpret_cast<const uint4 *>(xtab + exchange_offset<BW>(w, meta, m));
-    const uint32_t tlo = goq_perm(b1hi, b1lo, e.x);
-    const uint32_t thi = goq_perm(b1hi, b1lo, e.y);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 e = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(exchange_address<BW>(w, meta, m, vt));
     if constexpr (ACT == 0) {
-        b2lo = tlo ^ e.z;
-        b2hi = thi ^ e.w;
+        // fp16 high bytes: exchange the decoded bytes, flip sign bits
+        goq_decode_bytes<BW, ACT>(w, b1lo, b1hi);
+        b2lo = goq_perm(b1hi, b1lo, e.x) ^ e.z;
+        b2hi = goq_perm(b1hi, b1lo, e.y) ^ e.w;
     } else {
-        b2lo = negate_bytes(tlo, e.z);
-        b2hi = negate_bytes(thi, e.w);
+        // int8 (bw = 3): a sign flip is no bit flip, so the CODES are exchanged and looked up in
+        // the lattice and in the negated lattice; the mask picks per byte
+        static_assert(BW == 3, "int8 operands exist for bw = 3 only");
+        const uint32_t clo = w & 0x07070707u;
+        const uint32_t chi = (w >> 3) & 0x07070707u;
+        constexpr uint32_t PL = GoqLut<3, 1>::lo, PH = GoqLut<3, 1>::hi;
+        constexpr uint32_t NL = 0x00FEFCF8u, NH = 0x01020408u;       // -(b * 8) for codes 0..7
+        b1lo = goq_perm(PH, PL, clo);
+        b1hi = goq_perm(PH, PL, chi);
+        const uint32_t xlo = goq_perm(chi, clo, e.x);
+        const uint32_t xhi = goq_perm(chi, clo, e.y);
+        b2lo = (goq_perm(NH, NL, xlo) & e.z) | (goq_perm(PH, PL, xlo) & ~e.z);
+        b2hi = (goq_perm(NH, NL, xhi) & e.w) | (goq_perm(PH, PL, xhi) & ~e.w);
     }
 }
 
@@ -155,7 +158,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     using OpT = typename std::conditional<F16, f16x8, i32x4>::type;          // one MFMA operand
 
     __shared__ __attribute__((aligned(16))) unsigned char xsb[NBUF][TM * ROWB];
-    __shared__ __attribute__((aligned(16))) unsigned char xtab[64 * 16];
+    __shared__ __attribute__((aligned(16))) unsigned char xtab[64 * 16];        // exchange table
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -170,6 +173,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     const int n0 = nt * TN + wave * WN;
 
     if (tid < 64) *reinterpret_cast<uint4 *>(xtab + tid * 16) = exchange_entry<WACT>(tid);
+    const uint32_t vt = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)xtab;
 
     f32x16 Yacc[MS];
 #pragma unroll
@@ -279,13 +283,13 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     auto decode_step = [&](const Weights &w, int t, OpT &B1, OpT &B2) {
         if constexpr (F16) {
             uint32_t l1, h1, l2, h2;
-            decode_pair<BW, WACT>(word_of(w, t), w.meta, t, xtab, l1, h1, l2, h2);
+            decode_pair<BW, WACT>(word_of(w, t), w.meta, t, vt, l1, h1, l2, h2);
             B1 = widen8(l1, h1);
             B2 = widen8(l2, h2);
         } else {
             uint32_t l1, h1, l2, h2, l3, h3, l4, h4;
-            decode_pair<BW, WACT>(word_of(w, 2 * t), w.meta, 2 * t, xtab, l1, h1, l2, h2);
-            decode_pair<BW, ACT>(word_of(w, 2 * t + 1), w.meta, 2 * t + 1, xtab, l3, h3, l4, h4);
+            decode_pair<BW, WACT>(word_of(w, 2 * t), w.meta, 2 * t, vt, l1, h1, l2, h2);
+            decode_pair<BW, WACT>(word_of(w, 2 * t + 1), w.meta, 2 * t + 1, vt, l3, h3, l4, h4);
             B1 = i32x4{(int)l1, (int)h1, (int)l3, (int)h3};
             B2 = i32x4{(int)l2, (int)h2, (int)l4, (int)h4};
         }
@@ -305,7 +309,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
             // a lane's 8 dwords carry 16 of the 32 bits (lane group 0: c2, lane group 1: c1)
             uint32_t part = 0;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) part = (part << 2) | (word_of(w, t) >> 30);
+            for (int t = 0; t < 8; ++t) part = __builtin_amdgcn_alignbit(part, word_of(w, t), 30);
             const uint32_t other = __shfl_xor(part, 32);
             cw = kg ? (part | (other << 16)) : (other | (part << 16));
         } else {
