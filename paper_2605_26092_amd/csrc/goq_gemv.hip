@@ -59,6 +59,10 @@ constexpr int MAX_WG = GOQ_WGS;              // workgroups per launch (two per C
 constexpr int SW = 16;                   // units whose activation digits are resident in LDS
 constexpr int XG = 1024;                 // bytes of digits per macro-block: 4 k-groups x 8 digits x 32
 constexpr int XZ = 256;                  // zero bytes in front of the digit table
+#ifndef GOQ_CB
+#define GOQ_CB 16
+#endif
+constexpr int CB = GOQ_CB;               // parts a combining wavefront requests at a time
 constexpr int REGIONS = 8;               // scratch regions handed out round-robin to launches
 
 struct Region {
@@ -413,13 +417,13 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
     old = (unsigned)__builtin_amdgcn_readfirstlane((int)old);
     if (old == (unsigned)(bl - bf)) {
         float s = __hip_atomic_load(&S->partials[bf][1][rl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int w = bf + 1; w <= bl; w += 8) {            // eight independent loads at a time
-            float t[8];
+        for (int w = bf + 1; w <= bl; w += CB) {           // CB independent loads at a time
+            float t[CB];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < CB; ++i)
                 t[i] = __hip_atomic_load(&S->partials[min(w + i, bl)][0][rl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < CB; ++i)
                 if (w + i <= bl) s += t[i];
         }
         store(s);
