@@ -59,6 +59,25 @@ def activations_a8(tokens, inn, config_id=0, tensor_id=200):
     return xq, sx
 
 
+def activations_int(tokens, inn, bits, config_id=0, tensor_id=200):
+    """b_a-bit per-token symmetric integer activations in int8 containers (the paper's A3..A6
+    operating points): (int8 [tokens, in] with |x| <= 2^(bits-1) - 1, float32 scale [tokens])."""
+    r = rng(config_id, tensor_id)
+    x = r.normal(0.0, 1.0, size=(tokens, inn))
+    top = float((1 << (bits - 1)) - 1)
+    sx = (np.abs(x).max(axis=1) / top).astype(np.float32)
+    sx[sx == 0] = 1.0
+    xq = np.clip(np.rint(x / sx[:, None].astype(np.float64)), -top, top).astype(np.int8)
+    return xq, sx
+
+
+def pack_int4(xq):
+    """int8 values in [-8, 7], [tokens, in] -> packed int4 bytes [tokens, in / 2]: element 2 i in
+    the low nibble of byte i, two's complement (storage format only, no arithmetic)."""
+    u = (xq.astype(np.int16) & 0xF).astype(np.uint8)
+    return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+
+
 # W3 code histogram measured by quantising `weights()` with the GEO quantizer; codes follow the
 # canonical numbering (0:+1, 1:+.5, 2:+.25, 3:0, 4:-1, 5:-.5, 6:-.25, 7:-.125).
 _W3_HIST = np.array([0.0205, 0.1249, 0.2153, 0.2104, 0.0202, 0.1251, 0.1511, 0.1324])

@@ -50,7 +50,10 @@ enum {
     GOQ_EHIP = -4           /* a HIP runtime call failed (text in goq_last_error)       */
 };
 
-enum { GOQ_A16 = 0, GOQ_A8 = 1 };   /* activation type: fp16 | int8 (per-token scale)  */
+/* activation type (b_a-bit integer activations with scale s_x of Eq. 4): fp16 | int8 with a per-token
+ * scale | int4, two per byte (element 2 i in the low nibble of byte i, two's complement), with a
+ * per-token scale.  Integer activations of any width up to 8 bits (the paper's A6) go in as int8. */
+enum { GOQ_A16 = 0, GOQ_A8 = 1, GOQ_A4 = 2 };
 enum { GOQ_F16 = 0, GOQ_F32 = 1 };  /* output type                                      */
 
 #define GOQ_MAX_BATCH 8             /* problems per goq_gemv_batch call                 */
@@ -89,6 +92,7 @@ int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed
 /* Batch-1 layer output (Eq. 4 with one token).
  *   act = GOQ_A16: x is fp16 [in], sx must be NULL.
  *   act = GOQ_A8 : x is int8 [in], sx points to one fp32 scale (device).  Both bit widths.
+ *   act = GOQ_A4 : x is packed int4 [in / 2 bytes], sx as for GOQ_A8.
  *   y is [out] of ytype.  The PoT codes are decoded to 8-bit floats (a power of two is exact in
  *   E5M2) and b2 is rebuilt from b1 by a byte permute and a sign flip; the two slab dot products
  *   run on the 8-bit-float matrix instruction against x written as block fixed point (24 bits
@@ -121,8 +125,10 @@ int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *de
  *                  +128, which is no int8; the int8 activations are widened to fp16 on their way
  *                  into LDS and the fp16 MFMA is used -- every product is exact and a slab sum
  *                  needs at most 22 bits, so the fp32 accumulators hold the same exact integers.
- *   partials (optional, GOQ_A8 only, else NULL): int32 [tokens][out][in/128][2] receives the
- *   exact slab partials P_1, P_2 (in units of 2^-(E-1)). */
+ *   act = GOQ_A4 : X packed int4 [tokens][in / 2 bytes], sx fp32 [tokens]; unpacked to int8 (bw = 3)
+ *                  or widened to fp16 (bw = 4) on the way into LDS, then as GOQ_A8.
+ *   partials (optional, GOQ_A8 / GOQ_A4 only, else NULL): int32 [tokens][out][in/128][2] receives
+ *   the exact slab partials P_1, P_2 (in units of 2^-(E-1)). */
 int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t in,
              const void *packed, const void *X, const float *sx, void *Y, int ytype,
              int32_t *partials);

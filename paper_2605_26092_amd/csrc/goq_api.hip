@@ -88,10 +88,10 @@ static int check_gemv_desc(const char *fn, int bw, int act, const goq_gemv_desc 
 {
     int rc = check_shape(fn, bw, d.out, d.in);
     if (rc) return rc;
-    if (act != GOQ_A16 && act != GOQ_A8) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
     if (d.ytype != GOQ_F16 && d.ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "%s: bad output type %d", fn, d.ytype);
     if (!d.packed || !d.x || !d.y) return goq_set_error(GOQ_EINVAL, "%s: NULL pointer", fn);
-    if (act == GOQ_A8 && !d.sx) return goq_set_error(GOQ_EINVAL, "%s: int8 activations need sx", fn);
+    if (act != GOQ_A16 && !d.sx) return goq_set_error(GOQ_EINVAL, "%s: integer activations need sx", fn);
     if (act == GOQ_A16 && d.sx) return goq_set_error(GOQ_EINVAL, "%s: sx must be NULL for fp16 activations", fn);
     if (misaligned(d.packed, 16) || misaligned(d.x, 16) || misaligned(d.y, 16))
         return goq_set_error(GOQ_EINVAL, "%s: packed, x and y must be 16-byte aligned", fn);
@@ -126,10 +126,10 @@ int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t
     int rc = check_shape("goq_gemm", bw, out, in);
     if (rc) return rc;
     if (tokens <= 0 || tokens > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "goq_gemm: tokens = %lld out of range", (long long)tokens);
-    if (act != GOQ_A16 && act != GOQ_A8) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad activation type %d", act);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad activation type %d", act);
     if (ytype != GOQ_F16 && ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad output type %d", ytype);
     if (!packed || !X || !Y) return goq_set_error(GOQ_EINVAL, "goq_gemm: NULL pointer");
-    if (act == GOQ_A8 && !sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: int8 activations need sx");
+    if (act != GOQ_A16 && !sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: integer activations need sx");
     if (act == GOQ_A16 && sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: sx must be NULL for fp16 activations");
     if (act == GOQ_A16 && partials) return goq_set_error(GOQ_EINVAL, "goq_gemm: partials is only defined for int8 activations");
     if (misaligned(packed, 16) || misaligned(X, 16) || misaligned(Y, 16))

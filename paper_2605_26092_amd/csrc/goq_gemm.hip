@@ -148,7 +148,11 @@ template <int BW, int ACT, bool PART>
 __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a)
 {
     constexpr int CH = (BW == 3) ? 4 : 5;
-    constexpr bool F16 = (ACT != 1);                   // fp16 MFMA (ACT 0: fp16 x; ACT 2: int8 x widened)
+    // ACT: 0 fp16 x; 1 int8 x, int8 MFMA; 2 int8 x widened to fp16; 3 packed int4 x unpacked to
+    // int8, int8 MFMA; 4 packed int4 x widened to fp16.  2..4 stage x through registers.
+    constexpr bool F16 = (ACT == 0 || ACT == 2 || ACT == 4);       // fp16 MFMA
+    constexpr bool REGSTAGE = (ACT >= 2);
+    constexpr bool X4 = (ACT >= 3);                                // two activations per byte
     constexpr int WACT = F16 ? 0 : 1;                  // how the weights are decoded
     constexpr int XB = F16 ? 2 : 1;                    // bytes per activation in LDS
     constexpr int ROWB = GOQ_N * XB;                   // LDS row stride (XOR-swizzled, not padded)
@@ -239,44 +243,74 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                 (const __attribute__((address_space(1))) void *)(base + xoff[i]),
                 (__attribute__((address_space(3))) void *)(buf + (i * 256 + wave * 64) * 16), 16, 0, 0);
     };
-    // ACT == 2: the int8 activations pass through registers and are widened to fp16 on their way
-    // into LDS.  A thread moves NPS 16-byte pieces (16 activations each) per slab; piece cs of a
-    // row becomes the fp16 pieces 2 cs and 2 cs + 1.  int8 -> fp16 without a conversion
-    // instruction: 0x6400 | (x + 128) is the fp16 number 1024 + (x + 128); subtracting 1152 leaves x.
-    constexpr int NPS = TM * GOQ_N / 16 / 256;
+    // Register staging (ACT >= 2): integer activations pass through registers and are unpacked /
+    // widened on their way into LDS.  A thread moves NPS 16-byte pieces per slab; a piece holds
+    // 16 int8 or 32 int4 activations and becomes OUTP 16-byte pieces of the LDS row.
+    // int -> fp16 without a conversion instruction: 0x6400 | u is the fp16 number 1024 + u.
+    constexpr int SRCROW = X4 ? GOQ_N / 2 : GOQ_N;                 // bytes of a slab row in memory
+    constexpr int SPR = SRCROW / 16;                               // 16-byte source pieces per row
+    constexpr int NPS = (TM * SPR + 255) / 256;
+    constexpr int OUTP = ROWB / SPR / 16;                          // LDS pieces per source piece
+    const int64_t xpitch = X4 ? a.in / 2 : a.in;                   // bytes of a token row in memory
     uint32_t soff[NPS];
 #pragma unroll
     for (int i = 0; i < NPS; ++i) {
         const int S = i * 256 + tid;
-        int m = m0 + S / 8;
+        int m = m0 + S / SPR;
         m = m < a.tokens ? m : a.tokens - 1;
-        soff[i] = (uint32_t)(m - m0) * (uint32_t)a.in + (S % 8) * 16;
+        soff[i] = (uint32_t)(m - m0) * (uint32_t)xpitch + (S % SPR) * 16;
     }
     auto fetch_x = [&](int g, uint4 (&r)[NPS]) {
-        const unsigned char *base = reinterpret_cast<const unsigned char *>(a.X) + (int64_t)m0 * a.in + (int64_t)g * GOQ_N;
+        const unsigned char *base = reinterpret_cast<const unsigned char *>(a.X) + (int64_t)m0 * xpitch + (int64_t)g * SRCROW;
 #pragma unroll
         for (int i = 0; i < NPS; ++i) r[i] = *reinterpret_cast<const uint4 *>(base + soff[i]);
     };
+    // four int8 -> two registers of two fp16
+    auto widen_i8 = [](uint32_t d, uint32_t &h0, uint32_t &h1) {
+        const goq_half2 off = {(_Float16)1152.f, (_Float16)1152.f};
+        const uint32_t u = d ^ 0x80808080u;                        // x + 128
+        h0 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(goq_half2, goq_perm(0x64646464u, u, 0x04010400u)) - off);
+        h1 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(goq_half2, goq_perm(0x64646464u, u, 0x04030402u)) - off);
+    };
+    // eight int4 (element i in nibble i) -> two registers of four int8
+    auto unpack_i4 = [](uint32_t d, uint32_t &b0, uint32_t &b1) {
+        auto sext = [](uint32_t v) {      // per byte: low nibble, two's complement -> int8
+            return ((((v ^ 0x08080808u) | 0x80808080u) - 0x08080808u) ^ 0x80808080u);
+        };
+        const uint32_t ev = sext(d & 0x0F0F0F0Fu);                 // elements 0, 2, 4, 6
+        const uint32_t od = sext((d >> 4) & 0x0F0F0F0Fu);          // elements 1, 3, 5, 7
+        b0 = goq_perm(od, ev, 0x05010400u);                        // elements 0, 1, 2, 3
+        b1 = goq_perm(od, ev, 0x07030602u);                        // elements 4, 5, 6, 7
+    };
     auto write_x = [&](int g, const uint4 (&r)[NPS]) {
         unsigned char *buf = xsb[g % NBUF];
-        const goq_half2 off = {(_Float16)1152.f, (_Float16)1152.f};
 #pragma unroll
         for (int i = 0; i < NPS; ++i) {
             const int S = i * 256 + tid;
-            const int row = S / 8, cs = S % 8;
+            const int row = S / SPR, cs = S % SPR;
+            if (NPS * 256 > TM * SPR && S >= TM * SPR) continue;
             const uint32_t d[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-            uint32_t h[8];
+            uint32_t o[16];                                        // up to four LDS pieces
+            if constexpr (ACT == 2) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint32_t u = d[k] ^ 0x80808080u;
-                const goq_half2 lo = __builtin_bit_cast(goq_half2, goq_perm(0x64646464u, u, 0x04010400u)) - off;
-                const goq_half2 hi = __builtin_bit_cast(goq_half2, goq_perm(0x64646464u, u, 0x04030402u)) - off;
-                h[2 * k] = __builtin_bit_cast(uint32_t, lo);
-                h[2 * k + 1] = __builtin_bit_cast(uint32_t, hi);
+                for (int k = 0; k < 4; ++k) widen_i8(d[k], o[2 * k], o[2 * k + 1]);
+            } else if constexpr (ACT == 3) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) unpack_i4(d[k], o[2 * k], o[2 * k + 1]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t b0, b1;
+                    unpack_i4(d[k], b0, b1);
+                    widen_i8(b0, o[4 * k], o[4 * k + 1]);
+                    widen_i8(b1, o[4 * k + 2], o[4 * k + 3]);
+                }
             }
             unsigned char *dst = buf + row * ROWB;
-            *reinterpret_cast<uint4 *>(dst + (((2 * cs) ^ swz(row)) * 16)) = make_uint4(h[0], h[1], h[2], h[3]);
-            *reinterpret_cast<uint4 *>(dst + (((2 * cs + 1) ^ swz(row)) * 16)) = make_uint4(h[4], h[5], h[6], h[7]);
+#pragma unroll
+            for (int q = 0; q < OUTP; ++q)
+                *reinterpret_cast<uint4 *>(dst + (((OUTP * cs + q) ^ swz(row)) * 16)) =
+                    make_uint4(o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]);
         }
     };
     // decoded B operands (b1 and b2) of k-step t of a slab (H2, H4)
@@ -323,7 +357,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     Weights wd, wn;
     uint4 xr[NPS];
     load_weights(0, wd);
-    if constexpr (ACT == 2) {
+    if constexpr (REGSTAGE) {
         fetch_x(0, xr);
         write_x(0, xr);
         if (a.gn > 1) {
@@ -347,7 +381,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
         // (the weight request is unconditional, on a clamped slab index: past the last slab the
         // result is not used; the activation request comes last so that the wait below is exact)
         load_weights(min(g + 1, a.gn - 1), wn);
-        if constexpr (ACT == 2) {
+        if constexpr (REGSTAGE) {
             if (more2) fetch_x(g + 2, xr);
         } else {
             if (more2) stage_x(g + 2);
@@ -370,7 +404,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                 // last k-step of the slab.  Everything older than this slab's activation request
                 // has landed once at most NP vector-memory operations are outstanding (they return
                 // in order): slab g + 1's activations, requested a slab ago, and its weights.
-                if constexpr (ACT == 2) {
+                if constexpr (REGSTAGE) {
                     // (register path: slab g + 2 is written here; its buffer was last read before
                     // the previous slab's barrier, and it is first read after the next one)
                     if (more2) write_x(g + 2, xr);
@@ -431,8 +465,8 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
             const int m = m0 + 32 * i + 8 * (v / 4) + 4 * kg + (v % 4);
             if (m >= a.tokens || n >= a.out) continue;
             float y = Yacc[i][v];
-            if constexpr (ACT == 1) y *= a.sx[m] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
-            if constexpr (ACT == 2) y *= a.sx[m];
+            if constexpr (ACT != 0 && !F16) y *= a.sx[m] * (1.f / (float)(1 << ((1 << (BW - 1)) - 1)));
+            if constexpr (ACT != 0 && F16) y *= a.sx[m];
             if (a.ytype == GOQ_F32) reinterpret_cast<float *>(a.Y)[(int64_t)m * a.out + n] = y;
             else reinterpret_cast<__half *>(a.Y)[(int64_t)m * a.out + n] = __float2half(y);
         }
@@ -471,5 +505,7 @@ int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a);
     if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a);
     if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, a);
-    return launch<4, 2>(st, a);
+    if (bw == 4 && act == GOQ_A8) return launch<4, 2>(st, a);
+    if (bw == 3 && act == GOQ_A4) return launch<3, 3>(st, a);
+    return launch<4, 4>(st, a);
 }

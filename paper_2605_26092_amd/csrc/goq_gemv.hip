@@ -184,7 +184,7 @@ __device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, 
     if constexpr (ACT == 0) {
         const uint4 q = reinterpret_cast<const uint4 *>(x)[(int64_t)g * 16 + r];
         v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-    } else {
+    } else if constexpr (ACT == 1) {
         const uint2 q = reinterpret_cast<const uint2 *>(x)[(int64_t)g * 16 + r];
         const uint32_t b[2] = {q.x, q.y};
 #pragma unroll
@@ -192,6 +192,16 @@ __device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, 
             const int e0 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1)));
             const int e1 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1) + 8));
             const goq_half2 hv = {(_Float16)e0, (_Float16)e1};     // exact: |e| <= 128
+            v[d] = __builtin_bit_cast(uint32_t, hv);
+        }
+    } else {
+        // packed int4: element i of the run in nibble i of one dword
+        const uint32_t q = reinterpret_cast<const uint32_t *>(x)[(int64_t)g * 16 + r];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int e0 = (int)(q << (28 - 8 * d)) >> 28;         // sign-extended nibble 2 d
+            const int e1 = (int)(q << (24 - 8 * d)) >> 28;         // nibble 2 d + 1
+            const goq_half2 hv = {(_Float16)e0, (_Float16)e1};
             v[d] = __builtin_bit_cast(uint32_t, hv);
         }
     }
@@ -385,7 +395,7 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
         const float r = __shfl(t, lane & 15);
         if ((lane >> 4) == j) mine = r;
     }
-    if constexpr (ACT == 1) mine *= P.sx[0];
+    if constexpr (ACT != 0) mine *= P.sx[0];
     const int rl = wave * GOQ_ROWS + lane;                 // row inside the row group
     const int row = cur.rg * (WAVES * GOQ_ROWS) + rl;
     auto store = [&](float s) {
@@ -603,5 +613,7 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, nwg);
     if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a, nwg);
     if (bw == 4 && act == GOQ_A8) return launch<4, 1>(st, a, nwg);
+    if (bw == 3 && act == GOQ_A4) return launch<3, 2>(st, a, nwg);
+    if (bw == 4 && act == GOQ_A4) return launch<4, 2>(st, a, nwg);
     return launch<4, 0>(st, a, nwg);
 }

@@ -75,6 +75,26 @@ def test_gemm_a8_bit_exact_partials(oracle, bw, shape):
     assert np.array_equal(Y2.cpu().numpy(), Y.cpu().numpy())
 
 
+@pytest.mark.parametrize("bw", [3, 4])
+@pytest.mark.parametrize("shape", [(1, 16, 128), (17, 130, 384), (197, 768, 768), (300, 200, 1024)])
+def test_gemm_a4_bit_exact_partials(oracle, bw, shape):
+    """Packed 4-bit activations: int32 slab partials bit for bit against the oracle's integer
+    definition on the unpacked values."""
+    import paper_2605_26092_amd as goq
+    tokens, out, inn = shape
+    print("gemm a4 bw=%d tokens=%d out=%d in=%d" % (bw, tokens, out, inn), flush=True)
+    q = _quantize(oracle, bw, out, inn, 45)
+    Xq, sx = goq_inputs.activations_int(tokens, inn, 4, config_id=45, tensor_id=200 + tokens)
+    Xq[0, :8] = [-8, 7, -7, 0, 1, -1, -8, 7]
+    ref, rparts = oracle.gemm_a8(q, Xq, sx, threads=8, want_partials=True)
+    Y, parts = _gemm(goq, q, goq_inputs.pack_int4(Xq), goq.A4, goq.F32, sx_np=sx, want_partials=True)
+    assert np.array_equal(parts.cpu().numpy(), rparts)
+    what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
+    scale = (np.abs(Xq.astype(np.float64)) * sx[:, None].astype(np.float64)) @ what_abs.T
+    y = Y.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(y - ref) / np.maximum(scale, 1e-30)) <= 1e-5
+
+
 def test_gemm_edge_cases(oracle):
     import paper_2605_26092_amd as goq
     q = goq_inputs.canonical_random(3, 70, 256, config_id=43)

@@ -68,6 +68,24 @@ def test_gemv_a8(oracle, bw, shape):
     assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5
 
 
+@pytest.mark.parametrize("bw", [3, 4])
+@pytest.mark.parametrize("shape", [(1, 128), (17, 384), (200, 768), (1100, 1024)])
+def test_gemv_a4(oracle, bw, shape):
+    """Packed 4-bit activations (the W3/A4 and W4/A4 operating points): the definition is the
+    integer one of the int8 path on the unpacked values."""
+    import paper_2605_26092_amd as goq
+    out, inn = shape
+    print("gemv a4 bw=%d out=%d in=%d" % (bw, out, inn), flush=True)
+    q = _quantize(oracle, bw, out, inn, 34)
+    xq, sx = goq_inputs.activations_int(1, inn, 4, config_id=34, tensor_id=200 + out)
+    xq[0, :8] = [-8, 7, -7, 0, 1, -1, -8, 7]               # the full nibble range incl. -8
+    ref, _ = oracle.gemm_a8(q, xq, sx, threads=8)
+    y = _run_gemv(goq, q, goq_inputs.pack_int4(xq), goq.A4, goq.F32, sx_np=sx)
+    what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
+    scale = (np.abs(xq[0].astype(np.float64)) * float(sx[0])) @ what_abs.T
+    assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5
+
+
 def test_gemv_edge_cases(oracle):
     """all-zero codes, extreme fp16 activations, int8 saturation, single basis (c2 = 0)."""
     import paper_2605_26092_amd as goq

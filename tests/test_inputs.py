@@ -24,6 +24,23 @@ def test_a8_is_per_token_symmetric_int8():
     assert np.all(np.abs(xq.astype(int)).max(axis=1) == 127) and xq.min() >= -127
 
 
+def test_low_bit_activations_and_int4_packing():
+    for bits in (3, 4, 6):
+        xq, sx = goq_inputs.activations_int(8, 256, bits, 4)
+        top = (1 << (bits - 1)) - 1
+        assert xq.dtype == np.int8 and np.all(np.abs(xq.astype(int)).max(axis=1) == top)
+    xq, _ = goq_inputs.activations_int(8, 256, 4, 4)
+    xq[0, :4] = [-8, 7, -1, 0]
+    p = goq_inputs.pack_int4(xq)
+    assert p.shape == (8, 128) and p.dtype == np.uint8
+    lo = (p & 0xF).astype(np.int8)
+    hi = (p >> 4).astype(np.int8)
+    lo[lo > 7] -= 16
+    hi[hi > 7] -= 16
+    assert np.array_equal(lo, xq[:, 0::2]) and np.array_equal(hi, xq[:, 1::2])
+    assert p[0, 0] == 0x78 and p[0, 1] == 0x0F
+
+
 def test_canonical_random_ranges():
     for bw in (3, 4):
         q = goq_inputs.canonical_random(bw, 8, 256, 5)
