@@ -29,6 +29,7 @@ import goq_inputs  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 MFMA_I8_PEAK_TOPS = 5000.0
+FP64_VECTOR_PEAK_TFLOPS = 78.6
 
 
 def gemv_bytes(bw, shapes, ybytes=4):
@@ -157,8 +158,12 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
         if act == goq.A16:
             x = goq_inputs.activations_a16(tokens, inn, config_id=3, tensor_id=100 + idx, outlier_frac=0.01)
             sxs.append(None)
-        else:
+        elif act == goq.A8:
             x, sx = goq_inputs.activations_a8(tokens, inn, config_id=4, tensor_id=200 + idx)
+            sxs.append(torch.from_numpy(sx).to(dev))
+        else:
+            x, sx = goq_inputs.activations_int(tokens, inn, 4, config_id=4, tensor_id=200 + idx)
+            x = goq_inputs.pack_int4(x)
             sxs.append(torch.from_numpy(sx).to(dev))
         Xs.append(torch.from_numpy(x).to(dev))
         Ys.append(torch.zeros((tokens, out), dtype=torch.float16, device=dev))
@@ -180,11 +185,14 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
     torch.cuda.synchronize()
     ms = ev0.elapsed_time(ev1) / steps
     issued = 4.0 * tokens * sum(o * i for _, o, i in shapes)
-    peak = MFMA_F16_PEAK_TFLOPS if act == goq.A16 else MFMA_I8_PEAK_TOPS
+    # the peak of the matrix instruction the path runs on: fp16 for A16 and for bw = 4 with
+    # integer activations (widened to fp16), int8 otherwise
+    f16_path = act == goq.A16 or bw == 4
+    peak = MFMA_F16_PEAK_TFLOPS if f16_path else MFMA_I8_PEAK_TOPS
     tops = issued / (ms * 1e-3) / 1e12
-    return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, "A16" if act == goq.A16 else "A8"),
+    return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, {goq.A16: "A16", goq.A8: "A8", goq.A4: "A4"}[act]),
             "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1), "dense_equiv_TOPS": round(tops / 2, 1),
-            "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if act == goq.A16 else "TOP/s",
+            "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if f16_path else "TOP/s",
                          "frac": round(tops / peak, 4), "traffic": None}}
 
 
@@ -195,7 +203,7 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    act = goq.A16 if act_name == "A16" else goq.A8
+    act = {"A16": goq.A16, "A8": goq.A8, "A4": goq.A4}[act_name]
     packed, canon = [], []
     for idx, (_, out, inn) in enumerate(shapes):
         q = goq_inputs.canonical_random(bw, out, inn, config_id=3, tensor_id=300 + idx)
@@ -211,7 +219,7 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
         "metric": "PoT GEMV GB/s (% HBM peak) and GEMM TOPS (% MFMA peak), LLaMA-2-7B shapes",
         "value": g["issued_TOPS"], "unit": g["roofline"]["unit"], "n_gpus": 1, "steps": max(3, min(args.steps, 20)),
         "warmup": 2, "ms_per_step": g["ms_per_block"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if act_name == "A16" else "i8", "data": "synthetic",
+        "dtype": "f16" if (act_name == "A16" or bw == 4) else "i8", "data": "synthetic",
         "config": {"workload": name, "bw": bw, "act": act_name, "group": 128, "tokens": tokens, "matrices": len(shapes),
                    "issued_ops_per_step": 4.0 * tokens * sum(o * i for _, o, i in shapes),
                    "dense_equiv_TOPS": g["dense_equiv_TOPS"]},
@@ -223,8 +231,10 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
 
 def bench_quantize(args, shapes, bw, name):
     """The GEO quantizer on the device (goq_quantize): a step quantizes every matrix of the block.
-    Not the headline metric: reported in weights/s, with the HBM roofline of its own traffic
-    (2 B read + 1 B codes + 0.25 B metadata + 4/128 B coefficients written per weight)."""
+    Not the headline metric: reported in weights/s.  It is bound by fp64 vector arithmetic (one
+    lane per macro-block, sequential sums), so the roofline is the fp64 vector peak against the
+    method's fp64 operations per weight; its HBM traffic (2 B read + 1 B codes + 0.25 B metadata +
+    4/128 B coefficients written per weight) is reported under config."""
     import torch
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")
@@ -258,14 +268,20 @@ def bench_quantize(args, shapes, bw, name):
     nw = sum(o * i for _, o, i in shapes)
     nbytes = nw * (2 + 1 + 0.25 + 4.0 / 128)
     gbs = nbytes / (ms * 1e-3) / 1e9
+    # fp64 operations of the method per weight (Sec. 3.2 - 3.4, nearest state by midpoint compares):
+    # |w| and max 2, midpoint compares 2^(bw-1) + 1, <w,b1> and ||b1||^2 4, residual 2, cross terms
+    # 16 pairs x (2 mul, sub, abs, add) / 8 = 10, pair signs 2, <w,b2> and ||b2||^2 4
+    flop_per_weight = 2 + ((1 << (bw - 1)) + 1) + 4 + 2 + 10 + 2 + 4
+    tflops = nw * flop_per_weight / (ms * 1e-3) / 1e12
     res = {
         "metric": "GEO quantizer, weights/s (LLaMA-2-7B block shapes)", "value": round(nw / (ms * 1e-3) / 1e9, 2),
         "unit": "Gweights/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": name, "bw": bw, "group": 128, "matrices": len(shapes), "weights": int(nw),
-                   "llama2_7b_32_blocks_s": round(32 * ms * 1e-3, 4)},
-        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "quantize_kernel<%d>" % bw},
+                   "llama2_7b_32_blocks_s": round(32 * ms * 1e-3, 4), "hbm_GBps": round(gbs, 1),
+                   "fp64_ops_per_weight": flop_per_weight},
+        "roofline": {"bound": "alu", "achieved": round(tflops, 2), "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / FP64_VECTOR_PEAK_TFLOPS, 4), "traffic": None, "kernel": "quantize_kernel<%d>" % bw},
     }
     if args.no_cpu:
         res["cpu_baseline"] = None
@@ -294,8 +310,10 @@ def cpu_baseline_gemm(canon, shapes, bw, act_name, tokens):
     slab = 32 if act_name == "A16" else 64
     if act_name == "A16":
         x = goq_inputs.activations_a16(slab, inn, config_id=3, tensor_id=100, outlier_frac=0.01)
-    else:
+    elif act_name == "A8":
         x, sx = goq_inputs.activations_a8(slab, inn, config_id=4, tensor_id=200)
+    else:
+        x, sx = goq_inputs.activations_int(slab, inn, 4, config_id=4, tensor_id=200)
     reps, t0 = 0, time.perf_counter()
     while True:
         if act_name == "A16":
@@ -336,7 +354,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--settle", type=int, default=3000,
                     help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c5_gemm", "q_geo_w3", "q_geo_w4"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -362,6 +380,10 @@ def main():
         res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 4, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W4/A16")
     elif args.workload == "c4_gemm_a8":
         res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 3, "A8", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W3/A8")
+    elif args.workload == "c4_gemm_a4":
+        res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 3, "A4", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W3/A4")
+    elif args.workload == "c4_gemm_w4a8":
+        res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 4, "A8", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W4/A8")
     else:
         res = bench_gemm_only(args, goq_inputs.LLAMA2_70B_LAYER, 3, "A16", 512, "llama2-70b layer GEMMs, 512 tokens, W3/A16")
     print(json.dumps(res))

@@ -3,7 +3,8 @@
 // weights along `in` at a time.
 //
 // Steps per macro-block, in the paper's order: s_norm = ||w||_inf and v = w / s_norm (Sec. 3.2);
-// b1 = nearest lattice state of v, linear distance, exact ties toward the smaller magnitude;
+// b1 = nearest lattice state of v, linear distance, exact ties toward the smaller magnitude
+// (decided by comparing |w| with the midpoints scaled by s_norm, see nearest_code);
 // r = w - (<w, b1> / ||b1||^2) b1 (Eq. 1); per 8-weight micro-block the cross terms
 // t = x_i r_j - x_j r_i of the pairs (i, j = i xor s) of the four patterns, A_s = sum |t|,
 // s* = argmax (ties: smallest s), eta = sgn(t) (+1 at zero) (Sec. 3.3); b2 by the Theorem 1
@@ -29,16 +30,10 @@ constexpr int QT = 64;                       // macro-blocks (= threads) per wor
 constexpr int WSTRIDE = 65;                  // dwords per macro-block row of the weight tile (64 + 1 pad)
 constexpr int CSTRIDE = 33;                  // dwords per macro-block row of the code tile (32 + 1 pad)
 
+// fp16 -> fp64 is exact; the two hardware conversions (fp16 -> fp32 -> fp64) keep subnormals
 __device__ __forceinline__ double half_bits_to_double(uint32_t h)
 {
-    const int sign = (h >> 15) & 1;
-    const int exp = (h >> 10) & 0x1f;
-    const int man = h & 0x3ff;
-    double v;
-    if (exp == 0) v = ldexp((double)man, -24);                 // zero and subnormals
-    else if (exp == 31) v = man ? __builtin_nan("") : __builtin_inf();
-    else v = ldexp((double)(man | 0x400), exp - 25);
-    return sign ? -v : v;
+    return (double)(float)__builtin_bit_cast(_Float16, (unsigned short)h);
 }
 
 // round-to-nearest-even from fp64 straight to binary16 (no intermediate fp32)
@@ -70,23 +65,42 @@ __device__ __forceinline__ double code_value(int code)
     const int sign = (code >> (BW - 1)) & 1;
     const int e = code & (E - 1);
     if (!sign && e == E - 1) return 0.0;
-    const double v = ldexp(1.0, -e);
-    return sign ? -v : v;
+    // 2^-e assembled from its exponent field
+    return __longlong_as_double(((long long)sign << 63) | ((long long)(1023 - e) << 52));
 }
 
-// nearest lattice state in linear distance; an exact tie goes to the state of smaller magnitude
+// Nearest lattice state of v = w / s_norm in linear distance, an exact tie going to the state of
+// smaller magnitude -- decided without the division.  Between neighbouring magnitudes 2^-e and
+// 2^-(e+1) the midpoint is 0.75 * 2^-e; below the smallest magnitude m of a sign lies zero, with
+// midpoint m / 2.  |v| > mid is the same as |w| > mid * s_norm, and mid * s_norm is exact (a two-bit
+// number times an fp16 value).  The quotient's rounding cannot change a decision: |w| and
+// mid * s_norm are multiples of 2^-33 below 2^16, so unless they are equal they differ by more than
+// 2^-49 relative, a hundred times the quotient's rounding error, and v == mid exactly when they are
+// equal.  (Zero is nearer to a value than any state of the opposite sign.)
 template <int BW>
-__device__ __forceinline__ int nearest_code(double v)
+__device__ __forceinline__ int nearest_code(double w, double snorm)
 {
-    int best = 0;
-    double bestd = __builtin_inf(), bestabs = __builtin_inf();
+    constexpr int E = 1 << (BW - 1);
+    const bool neg = w < 0.0;
+    const double a = fabs(w);
+    const int emin = neg ? E - 1 : E - 2;          // exponent of the smallest magnitude of this sign
+    int e = emin + 1;                              // emin + 1 stands for zero
+    // largest magnitude whose lower midpoint a exceeds
+    double mid = 0.75 * snorm;                     // between 2^0 and 2^-1
+    int found = 0;
 #pragma unroll
-    for (int c = 0; c < (1 << BW); ++c) {
-        const double l = code_value<BW>(c);
-        const double d = fabs(v - l);
-        if (d < bestd || (d == bestd && fabs(l) < bestabs)) { best = c; bestd = d; bestabs = fabs(l); }
+    for (int k = 0; k < E; ++k) {
+        if (k < emin) {
+            if (!found && a > mid) { e = k; found = 1; }
+            mid *= 0.5;
+        } else if (k == emin) {
+            // below the smallest magnitude 2^-emin lies zero: midpoint 2^-(emin+1)
+            const double mz = __longlong_as_double((long long)(1023 - emin - 1) << 52) * snorm;
+            if (!found && a > mz) { e = k; found = 1; }
+        }
     }
-    return best;
+    if (e == emin + 1) return E - 1;               // the zero state (sign 0, e = E - 1)
+    return (neg ? E : 0) | e;
 }
 
 template <int BW>
@@ -129,7 +143,7 @@ __global__ __launch_bounds__(QT) void quantize_kernel(const uint32_t *__restrict
                 for (int kk = 0; kk < 4; ++kk) {
                     const int k = 4 * k4 + kk;
                     const double wk = W(k);
-                    const int c = nearest_code<BW>(wk / snorm);
+                    const int c = nearest_code<BW>(wk, snorm);
                     pack |= (uint32_t)c << (8 * kk);
                     const double b = code_value<BW>(c);
                     wb1 += wk * b;
