@@ -4,6 +4,7 @@
  * A plain, slow, scalar fp64 implementation of
  *   (Q) the data-free GEO-mode analytical quantizer          (Sec. 3.2, 3.3, 3.4)
  *   (D) the dual power-of-two (PoT) inner product of a layer  (Sec. 3.5, Eq. 4)
+ *   (R) the REF-mode activation-aware coefficients            (Sec. 3.4, Eq. 3)
  * written from the paper's equations in the paper's order.  It shares no code
  * with the HIP library; only tests, the smoke check and the benchmark's
  * cpu_baseline leg may call it.
@@ -12,7 +13,10 @@
  * orthogonality over all 64 (pattern, sign) choices, brute force over the
  * lattice per element and over the 64 exchange candidates per micro-block,
  * generic least squares for the coefficients, dense fp64 matmul of the
- * dequantised matrix, exact integer partials, a hand-derived worked example.
+ * dequantised matrix, exact integer partials, a hand-derived worked example;
+ * for (R): generic least squares on the ridge-augmented system, the closed form
+ * for identity calibration inputs (which ties it to Eq. 2), exact recovery of
+ * weights that lie in the span of the two bases.
  * Parity unpinned by the paper itself (pinned only by this build's readings):
  * the 4-bit lattice, rounding ties, the all-zero block, the code numbering and
  * the fp16 storage of coefficients.
@@ -351,6 +355,61 @@ int goq_oracle_gemm_a8(int bw, int64_t tokens, int64_t out, int64_t in,
         free(i1);
     }
     return fail ? -(10 + fail) : 0;
+}
+
+/* ---------------------------------------------------------------- Part R: REF mode (Sec. 3.4, Eq. 3)
+ *
+ * Activation-aware refinement of the two block coefficients.  The bases b1, b2 of every macro-block
+ * are those of the canonical arrays (they are built without looking at activations); only c1, c2 are
+ * re-solved.  For output channel o and macro-block g, with the M calibration rows
+ * X_q = x[:, 128 g .. 128 g + 127] (M x 128):
+ *     Y = X_q w                         the slab's output for the original weights
+ *     A = [X_q b1, X_q b2]              (M x 2) the responses of the two bases
+ *     c* = (A^T A + lambda I)^-1 A^T Y  ridge regression (the paper uses lambda = 1e-4)
+ * w: float32 holding fp16-representable values [out][in]; x: fp16 bit patterns [tokens][in].
+ * craw (optional): the unrounded solution [out][in/128][2]; c1, c2: rounded to fp16. */
+int goq_oracle_ref_coefficients(int bw, int64_t tokens, int64_t out, int64_t in, const float *w,
+                                const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs,
+                                const uint16_t *x, double lambda, double *craw,
+                                uint16_t *c1, uint16_t *c2, int threads)
+{
+    if ((bw != 3 && bw != 4) || tokens <= 0 || out <= 0 || in <= 0 || in % GOQ_N || lambda < 0.0) return -1;
+    int64_t gn = in / GOQ_N;
+    int fail = 0;
+#pragma omp parallel for num_threads(threads > 0 ? threads : 1) schedule(static)
+    for (int64_t o = 0; o < out; ++o) {
+        double *b1 = (double *)malloc(sizeof(double) * in * 2);
+        if (!b1) { fail = 1; continue; }
+        double *b2 = b1 + in;
+        row_bases(bw, in, codes + o * in, pattern + o * in / GOQ_G, signs + o * in / GOQ_G, b1, b2);
+        for (int64_t g = 0; g < gn; ++g) {
+            double g11 = 0.0, g12 = 0.0, g22 = 0.0, r1 = 0.0, r2 = 0.0;      /* A^T A and A^T Y */
+            for (int64_t t = 0; t < tokens; ++t) {
+                double y = 0.0, a1 = 0.0, a2 = 0.0;
+                for (int64_t k = g * GOQ_N; k < (g + 1) * GOQ_N; ++k) {
+                    double xv = goq_oracle_half_to_double(x[t * in + k]);
+                    y += xv * (double)w[o * in + k];
+                    a1 += xv * b1[k];
+                    a2 += xv * b2[k];
+                }
+                g11 += a1 * a1; g12 += a1 * a2; g22 += a2 * a2;
+                r1 += a1 * y;   r2 += a2 * y;
+            }
+            g11 += lambda;
+            g22 += lambda;
+            double det = g11 * g22 - g12 * g12;
+            double s1 = 0.0, s2 = 0.0;
+            if (det != 0.0) {                       /* det = 0 only with lambda = 0 and dependent columns */
+                s1 = (g22 * r1 - g12 * r2) / det;
+                s2 = (g11 * r2 - g12 * r1) / det;
+            }
+            if (craw) { craw[(o * gn + g) * 2] = s1; craw[(o * gn + g) * 2 + 1] = s2; }
+            c1[o * gn + g] = goq_oracle_double_to_half(s1);
+            c2[o * gn + g] = goq_oracle_double_to_half(s2);
+        }
+        free(b1);
+    }
+    return fail ? -2 : 0;
 }
 
 int goq_oracle_max_threads(void)

@@ -171,3 +171,30 @@ def gemm_a8(q, x_i8, sx, threads=1, want_partials=False):
     if rc:
         raise ValueError("goq_oracle_gemm_a8 failed: %d" % rc)
     return y, parts
+
+
+def ref_coefficients(q, w, x_f16, lam=1e-4, threads=1):
+    """REF mode (Eq. 3): canonical arrays q (bases), fp16-valued weights w [out, in], calibration
+    inputs x_f16 [tokens, in] -> (dict like q with the re-solved c1, c2, unrounded c [out, gn, 2])."""
+    w32 = _c(np.asarray(w, dtype=np.float32), np.float32)
+    x = _c(np.asarray(x_f16, dtype=np.float16), np.float16)
+    tokens, inn = x.shape
+    out = q["codes"].shape[0]
+    assert w32.shape == (out, inn) and q["codes"].shape[1] == inn
+    gn = inn // N
+    craw = np.zeros((out, gn, 2), np.float64)
+    c1 = np.zeros((out, gn), np.uint16)
+    c2 = np.zeros((out, gn), np.uint16)
+    rc = lib().goq_oracle_ref_coefficients(ctypes.c_int(q["bw"]), ctypes.c_int64(tokens), ctypes.c_int64(out),
+                                           ctypes.c_int64(inn), _p(w32, ctypes.c_float),
+                                           _p(_c(q["codes"], np.uint8), ctypes.c_uint8),
+                                           _p(_c(q["pattern"], np.uint8), ctypes.c_uint8),
+                                           _p(_c(q["signs"], np.uint8), ctypes.c_uint8),
+                                           _p(x.view(np.uint16), ctypes.c_uint16), ctypes.c_double(lam),
+                                           _p(craw, ctypes.c_double), _p(c1, ctypes.c_uint16),
+                                           _p(c2, ctypes.c_uint16), ctypes.c_int(threads))
+    if rc:
+        raise ValueError("goq_oracle_ref_coefficients failed: %d" % rc)
+    r = dict(q)
+    r["c1"], r["c2"] = c1, c2
+    return r, craw
