@@ -302,6 +302,81 @@ def bench_quantize(args, shapes, bw, name):
     return res
 
 
+def bench_ref(args, shapes, bw, tokens, name):
+    """REF-mode coefficients on the device (goq_ref_coefficients): a step re-solves (c1, c2) of every
+    macro-block of every matrix of the block from `tokens` calibration rows.  Not the headline
+    metric; fp64 arithmetic, so the roofline is the fp64 vector peak against the operations of the
+    Gram-matrix formulation (2 T 128 in per matrix for the Gram matrices, 4 * 128^2 + 10 * 128 per
+    output channel and macro-block for the two products and five dot products)."""
+    import torch
+    import paper_2605_26092_amd as goq
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    bufs, flops = [], 0.0
+    for idx, (_, out, inn) in enumerate(shapes):
+        q = goq_inputs.canonical_random(bw, out, inn, config_id=7, tensor_id=300 + idx)
+        w = goq_inputs.weights(out, inn, config_id=7, tensor_id=idx)
+        x = goq_inputs.activations_a16(tokens, inn, config_id=7, tensor_id=100 + idx, outlier_frac=0.01)
+        gn = inn // 128
+        bufs.append((out, inn, torch.from_numpy(w.view(np.int16)).to(dev), torch.from_numpy(q["codes"]).to(dev),
+                     torch.from_numpy(q["pattern"]).to(dev), torch.from_numpy(q["signs"]).to(dev),
+                     torch.from_numpy(x.view(np.int16)).to(dev),
+                     torch.empty(goq.ref_workspace_bytes(inn), dtype=torch.uint8, device=dev),
+                     torch.empty((out, gn), dtype=torch.int16, device=dev),
+                     torch.empty((out, gn), dtype=torch.int16, device=dev), (q, w, x)))
+        flops += 2.0 * tokens * 128 * inn + out * gn * (4.0 * 128 * 128 + 10 * 128)
+    stream = torch.cuda.current_stream()
+    steps, warmup = max(3, min(args.steps, 20)), 2
+
+    def step():
+        for out, inn, wd, c, p, sg, xd, ws, c1, c2, _ in bufs:
+            goq.ref_coefficients(bw, tokens, out, inn, wd, c, p, sg, xd, 1e-4, ws, None, c1, c2, stream=stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    nw = sum(o * i for _, o, i in shapes)
+    tflops = flops / (ms * 1e-3) / 1e12
+    res = {
+        "metric": "REF-mode coefficients, weights/s (LLaMA-2-7B block shapes)", "value": round(nw / (ms * 1e-3) / 1e9, 2),
+        "unit": "Gweights/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": name, "bw": bw, "group": 128, "matrices": len(shapes), "weights": int(nw),
+                   "calibration_tokens": tokens, "lambda": 1e-4, "fp64_ops_per_step": flops,
+                   "llama2_7b_32_blocks_s": round(32 * ms * 1e-3, 4)},
+        "roofline": {"bound": "alu", "achieved": round(tflops, 2), "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / FP64_VECTOR_PEAK_TFLOPS, 4), "traffic": None, "kernel": "ref_solve_kernel<%d>" % bw},
+    }
+    if args.no_cpu:
+        res["cpu_baseline"] = None
+    else:
+        from oracle import goq_oracle as O
+        threads = min(O.max_threads(), os.cpu_count() or 1)
+        q, w, x = bufs[0][10]
+        rows, tk = 64, 64
+        qs = {k: (v[:rows] if isinstance(v, np.ndarray) else v) for k, v in q.items()}
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            O.ref_coefficients(qs, w[:rows], x[:tk], lam=1e-4, threads=threads)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el > 10.0 or reps >= 50:
+                break
+        # weights/s at the benchmark's token count: the oracle's cost is linear in the tokens
+        res["cpu_baseline"] = {"value": round(rows * w.shape[1] * reps / el / 1e9 * tk / tokens, 6), "unit": "Gweights/s",
+                               "cores": threads, "kind": "oracle",
+                               "sample": "%d pass(es) over the first %d rows of the first matrix with %d tokens (scaled to %d tokens), %.1f s"
+                               % (reps, rows, tk, tokens, el)}
+    return res
+
+
 def cpu_baseline_gemm(canon, shapes, bw, act_name, tokens):
     """The oracle on a token slab of the first matrix (all outputs), issued-op rate."""
     from oracle import goq_oracle as O
@@ -354,7 +429,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--settle", type=int, default=3000,
                     help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -374,6 +449,8 @@ def main():
     elif args.workload in ("q_geo_w3", "q_geo_w4"):
         bw = 3 if args.workload == "q_geo_w3" else 4
         res = bench_quantize(args, goq_inputs.LLAMA2_7B_BLOCK, bw, "GEO quantization of a llama2-7b decoder block, W%d" % bw)
+    elif args.workload == "ref_w3":
+        res = bench_ref(args, goq_inputs.LLAMA2_7B_BLOCK, 3, 512, "REF coefficients of a llama2-7b decoder block, W3, 512 calibration tokens")
     elif args.workload == "c3_gemm_w3":
         res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W3/A16")
     elif args.workload == "c3_gemm_w4":

@@ -80,6 +80,23 @@ int goq_packed_bytes(int bw, int64_t out, int64_t in, size_t *bytes);
 int goq_quantize(void *stream, int bw, int64_t out, int64_t in, const uint16_t *w,
                  uint8_t *codes, uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
 
+/* REF-mode (activation-aware) block coefficients (Sec. 3.4, Eq. 3) on the device.  The bases b1, b2
+ * are those of the canonical arrays (codes, pattern, signs: from goq_quantize or elsewhere); for
+ * every output channel and 128-wide macro-block the pair (c1, c2) is re-solved by ridge regression
+ * on the calibration inputs X (fp16 [tokens][in], row-major, 16-byte aligned):
+ *     Y = X_q w,  A = [X_q b1, X_q b2],  c* = (A^T A + lambda I)^-1 A^T Y        (the paper: lambda = 1e-4)
+ * with X_q the macro-block's 128 columns of X and w the fp16 weights [out][in].  Computed in fp64
+ * through the macro-block's Gram matrix X_q^T X_q, which all output channels share; `workspace` is
+ * caller-owned device memory of goq_ref_workspace_bytes(in) bytes (16-byte aligned), used only
+ * during the call.  c1, c2 [out][in/128] receive the fp16 bit patterns; craw (optional, may be
+ * NULL) receives the unrounded pairs as double [out][in/128][2].  lambda >= 0; a singular system
+ * (possible only at lambda = 0) gives c1 = c2 = 0.  codes must be 8-byte aligned. */
+int goq_ref_workspace_bytes(int64_t in, size_t *bytes);      /* *bytes is a host pointer */
+int goq_ref_coefficients(void *stream, int bw, int64_t tokens, int64_t out, int64_t in, const uint16_t *w,
+                         const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs,
+                         const uint16_t *X, double lambda, void *workspace, double *craw,
+                         uint16_t *c1, uint16_t *c2);
+
 /* Stored representation (Sec. 3.3 item 3): canonical arrays -> packed buffer, on the device. */
 int goq_pack(void *stream, int bw, int64_t out, int64_t in,
              const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs,

@@ -5,7 +5,7 @@ library (libgoq.so, built in-tree by paper_2605_26092_amd/build.py); this packag
 pointers.  torch is used for device memory and streams, nothing else.
 """
 from .binding import (A4, A16, A8, F16, F32, GoqError, gemm, gemv, gemv_batch, last_error, lib, pack,
-                      packed_bytes, quantize, unpack, version)
+                      packed_bytes, quantize, ref_coefficients, ref_workspace_bytes, unpack, version)
 
 __all__ = ["A4", "A16", "A8", "F16", "F32", "GoqError", "gemm", "gemv", "gemv_batch", "last_error", "lib",
-           "pack", "packed_bytes", "quantize", "unpack", "version"]
+           "pack", "packed_bytes", "quantize", "ref_coefficients", "ref_workspace_bytes", "unpack", "version"]

@@ -15,7 +15,8 @@ F16, F32 = 0, 1
 OK, EINVAL, ESHAPE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
 MAX_BATCH = 8
 
-EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_pack", "goq_unpack",
+EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_ref_workspace_bytes",
+           "goq_ref_coefficients", "goq_pack", "goq_unpack",
            "goq_gemv", "goq_gemv_batch", "goq_gemm"]
 
 
@@ -43,6 +44,8 @@ def lib():
         L.goq_last_error.restype = ctypes.c_char_p
         L.goq_packed_bytes.argtypes = [i, i64, i64, ctypes.POINTER(ctypes.c_size_t)]
         L.goq_quantize.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.goq_ref_workspace_bytes.argtypes = [i64, ctypes.POINTER(ctypes.c_size_t)]
+        L.goq_ref_coefficients.argtypes = [vp, i, i64, i64, i64, vp, vp, vp, vp, vp, ctypes.c_double, vp, vp, vp, vp]
         L.goq_pack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_unpack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_gemv.argtypes = [vp, i, i, i64, i64, vp, vp, vp, vp, i]
@@ -89,6 +92,17 @@ def packed_bytes(bw, out, inn):
 def quantize(bw, out, inn, w, codes, pattern, signs, c1, c2, stream=None):
     _check(lib().goq_quantize(_stream(stream), bw, out, inn, _ptr(w), _ptr(codes), _ptr(pattern), _ptr(signs),
                               _ptr(c1), _ptr(c2)))
+
+
+def ref_workspace_bytes(inn):
+    n = ctypes.c_size_t(0)
+    _check(lib().goq_ref_workspace_bytes(inn, ctypes.byref(n)))
+    return n.value
+
+
+def ref_coefficients(bw, tokens, out, inn, w, codes, pattern, signs, X, lam, workspace, craw, c1, c2, stream=None):
+    _check(lib().goq_ref_coefficients(_stream(stream), bw, tokens, out, inn, _ptr(w), _ptr(codes), _ptr(pattern),
+                                      _ptr(signs), _ptr(X), float(lam), _ptr(workspace), _ptr(craw), _ptr(c1), _ptr(c2)))
 
 
 def pack(bw, out, inn, codes, pattern, signs, c1, c2, packed, stream=None):

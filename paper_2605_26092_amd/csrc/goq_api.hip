@@ -62,6 +62,33 @@ int goq_quantize(void *stream, int bw, int64_t out, int64_t in, const uint16_t *
     return goq_launch_quantize((hipStream_t)stream, bw, out, in, w, codes, pattern, signs, c1, c2);
 }
 
+int goq_ref_workspace_bytes(int64_t in, size_t *bytes)
+{
+    if (!bytes) return goq_set_error(GOQ_EINVAL, "goq_ref_workspace_bytes: bytes is NULL");
+    if (in <= 0 || in % GOQ_N) return goq_set_error(GOQ_ESHAPE, "goq_ref_workspace_bytes: in = %lld must be a positive multiple of 128", (long long)in);
+    *bytes = (size_t)(in / GOQ_N) * GOQ_N * GOQ_N * sizeof(double);
+    return GOQ_OK;
+}
+
+int goq_ref_coefficients(void *stream, int bw, int64_t tokens, int64_t out, int64_t in, const uint16_t *w,
+                         const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs, const uint16_t *X,
+                         double lambda, void *workspace, double *craw, uint16_t *c1, uint16_t *c2)
+{
+    int rc = check_shape("goq_ref_coefficients", bw, out, in);
+    if (rc) return rc;
+    if (tokens <= 0 || tokens > (1 << 24))
+        return goq_set_error(GOQ_ESHAPE, "goq_ref_coefficients: tokens = %lld out of range", (long long)tokens);
+    if (!(lambda >= 0.0) || lambda > 1e300)
+        return goq_set_error(GOQ_EINVAL, "goq_ref_coefficients: lambda must be finite and >= 0");
+    if (!w || !codes || !pattern || !signs || !X || !workspace || !c1 || !c2)
+        return goq_set_error(GOQ_EINVAL, "goq_ref_coefficients: NULL pointer");
+    if (misaligned(X, 16) || misaligned(workspace, 16) || misaligned(codes, 8) || misaligned(w, 2) ||
+        misaligned(c1, 2) || misaligned(c2, 2) || misaligned(craw, 8))
+        return goq_set_error(GOQ_EINVAL, "goq_ref_coefficients: X and workspace must be 16-byte aligned, codes 8-byte");
+    return goq_launch_ref((hipStream_t)stream, bw, tokens, out, in, w, codes, pattern, signs, X, lambda, workspace,
+                          craw, c1, c2);
+}
+
 int goq_pack(void *stream, int bw, int64_t out, int64_t in, const uint8_t *codes, const uint8_t *pattern,
              const uint8_t *signs, const uint16_t *c1, const uint16_t *c2, void *packed)
 {

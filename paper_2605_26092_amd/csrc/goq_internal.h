@@ -15,6 +15,9 @@ int goq_launch_unpack(hipStream_t st, int bw, int64_t out, int64_t in, const voi
                       uint8_t *codes, uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
 int goq_launch_quantize(hipStream_t st, int bw, int64_t out, int64_t in, const uint16_t *w, uint8_t *codes,
                         uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
+int goq_launch_ref(hipStream_t st, int bw, int64_t tokens, int64_t out, int64_t in, const uint16_t *w,
+                   const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs, const uint16_t *X,
+                   double lambda, void *workspace, double *craw, uint16_t *c1, uint16_t *c2);
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs);
 int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out, int64_t in,
                     const void *packed, const void *X, const float *sx, void *Y, int ytype,
