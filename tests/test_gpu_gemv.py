@@ -153,3 +153,37 @@ def test_gemv_config1_full_size(oracle, bw):
         y = _run_gemv(goq, q, x, goq.A16, ytype)
         e1, _ = gu.a16_errors(y, ref, None)
         assert e1 <= TOL, (ytype, e1)
+
+
+def test_gemv_two_streams_in_flight_and_repeatable(oracle):
+    """Launches on two streams share the library's scratch regions round-robin (at most 8 in flight):
+    interleaved launches of two different layers, whose row groups are split over many workgroups,
+    must all give the single-launch result, bit for bit (the combine order is fixed)."""
+    import paper_2605_26092_amd as goq
+    torch = gu.torch_cuda()
+    layers = []
+    for i, (out, inn) in enumerate([(1500, 2048), (700, 4096)]):
+        q = _quantize(oracle, 3, out, inn, 36 + i)
+        x = goq_inputs.activations_a16(1, inn, config_id=36, tensor_id=i)
+        packed = gu.pack_layer(goq, q)
+        xd = gu.to_dev(x.reshape(-1))
+        y0 = torch.zeros(out, dtype=torch.float32, device="cuda")
+        goq.gemv(3, goq.A16, out, inn, packed, xd, None, y0, goq.F32)
+        torch.cuda.synchronize()
+        ref = oracle.gemm_a16(q, x, threads=8)[0]
+        e1, _ = gu.a16_errors(y0.cpu().numpy(), ref, None)
+        assert e1 <= TOL
+        layers.append((out, inn, packed, xd, y0))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep in range(6):
+        for s, (out, inn, packed, xd, y0) in zip(streams, layers):
+            y = torch.full((out,), float("nan"), dtype=torch.float32, device="cuda")
+            with torch.cuda.stream(s):
+                goq.gemv(3, goq.A16, out, inn, packed, xd, None, y, goq.F32, stream=s)
+            outs.append((y, y0))
+        if rep % 3 == 2:
+            torch.cuda.synchronize()          # never more than 8 launches in flight
+    torch.cuda.synchronize()
+    for y, y0 in outs:
+        assert torch.equal(y, y0)
