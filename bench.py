@@ -122,7 +122,7 @@ def bench_gemv(args, shapes, bw, name):
                    "cache_resident_GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "gemv_kernel<%d,0>" % bw, "avg_launch_us": round(dev_ms * 1e3, 3)},
+                     "kernel": gemv_kernel_name(bw, shapes), "avg_launch_us": round(dev_ms * 1e3, 3)},
     }
     # HBM traffic per launch from the committed counter runs (FETCH_SIZE + WRITE_SIZE, scaled), if present
     try:
@@ -145,6 +145,13 @@ def bench_gemv(args, shapes, bw, name):
         res["gemm"] = bench_gemm_block(args, shapes, bw, goq.A16, packed0, args.gemm_tokens)
     res["cpu_baseline"] = cpu_baseline_gemv(canon, shapes, bw, alg_bytes) if not args.no_cpu else None
     return res
+
+
+def gemv_kernel_name(bw, shapes):
+    """The kernel the library's automatic choice launches for these layers (see goq_gemv_select in
+    include/goq.h): the row-owner kernel up to 512 (bw = 3) or 1024 (bw = 4) 16-row tiles."""
+    tiles = sum((out + 15) // 16 for _, out, _ in shapes)
+    return ("gemv_rows_kernel<%d,0>" if tiles <= (512 if bw == 3 else 1024) else "gemv_kernel<%d,0>") % bw
 
 
 def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):

@@ -134,6 +134,20 @@ typedef struct goq_gemv_desc {
 } goq_gemv_desc;
 int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *descs);
 
+/* Which of the two batch-1 kernels goq_gemv / goq_gemv_batch launch (process-wide, takes effect
+ * with the next call; both kernels compute the same sums, H2..H6 of Sec. 3.3, and both accept
+ * every shape):
+ *   GOQ_GEMV_AUTO   (default) by size: launches of at most 8192 (bw = 3) or 16384 (bw = 4)
+ *                   output rows in all, each problem's rows rounded up to 16, go to the
+ *                   row-owner kernel, everything else streams;
+ *   GOQ_GEMV_STREAM the streaming kernel: equal contiguous pieces of the launch's weight bytes
+ *                   per workgroup, split row groups combined through the scratch area;
+ *   GOQ_GEMV_ROWS   the row-owner kernel: one workgroup per 16 output rows over the whole depth,
+ *                   partial sums combined in LDS (no scratch).
+ * Returns GOQ_EINVAL for any other value. */
+enum { GOQ_GEMV_AUTO = 0, GOQ_GEMV_STREAM = 1, GOQ_GEMV_ROWS = 2 };
+int goq_gemv_select(int kernel);
+
 /* Many-token layer output (Eq. 4), Y[tokens][out] = X[tokens][in] * W^T.
  *   act = GOQ_A16: X fp16, sx NULL; PoT codes are decoded to fp16 operands of the fp16 MFMA,
  *                  fp32 accumulation.

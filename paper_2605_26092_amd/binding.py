@@ -14,10 +14,11 @@ A16, A8, A4 = 0, 1, 2
 F16, F32 = 0, 1
 OK, EINVAL, ESHAPE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
 MAX_BATCH = 8
+GEMV_AUTO, GEMV_STREAM, GEMV_ROWS = 0, 1, 2
 
 EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_ref_workspace_bytes",
            "goq_ref_coefficients", "goq_pack", "goq_unpack",
-           "goq_gemv", "goq_gemv_batch", "goq_gemm"]
+           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemm"]
 
 
 class GoqError(RuntimeError):
@@ -50,6 +51,7 @@ def lib():
         L.goq_unpack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_gemv.argtypes = [vp, i, i, i64, i64, vp, vp, vp, vp, i]
         L.goq_gemv_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc)]
+        L.goq_gemv_select.argtypes = [i]
         L.goq_gemm.argtypes = [vp, i, i, i64, i64, i64, vp, vp, vp, vp, i, vp]
         _lib = L
     return _lib
@@ -125,6 +127,10 @@ def make_descs(problems):
     for d, (out, inn, packed, x, sx, y, ytype) in zip(arr, problems):
         d.out, d.in_, d.packed, d.x, d.sx, d.y, d.ytype = out, inn, _ptr(packed), _ptr(x), _ptr(sx), _ptr(y), ytype
     return arr
+
+
+def gemv_select(kernel):
+    _check(lib().goq_gemv_select(kernel))
 
 
 def gemv_batch(bw, act, problems, stream=None):

@@ -135,6 +135,14 @@ int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in, const void 
     return goq_launch_gemv((hipStream_t)stream, bw, act, 1, &d);
 }
 
+int goq_gemv_select(int kernel)
+{
+    if (kernel != GOQ_GEMV_AUTO && kernel != GOQ_GEMV_STREAM && kernel != GOQ_GEMV_ROWS)
+        return goq_set_error(GOQ_EINVAL, "goq_gemv_select: kernel = %d is none of GOQ_GEMV_AUTO/STREAM/ROWS", kernel);
+    goq_gemv_set_kernel(kernel);
+    return GOQ_OK;
+}
+
 int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *descs)
 {
     if (!descs) return goq_set_error(GOQ_EINVAL, "goq_gemv_batch: descs is NULL");

@@ -82,6 +82,7 @@ struct GemvProblem {
     int rbn;         // row blocks
     int rgroups;     // row groups
     int begin;       // first unit of this problem in the linear unit sequence
+    int bb;          // first 16-row block of this problem in the grid of the row-owner kernel
 };
 
 struct GemvArgs {
@@ -291,74 +292,95 @@ __device__ __forceinline__ void stage_window(const GemvArgs &a, int u0, int ns, 
     }
 }
 
+// ---- one 16-row slice of a macro-block (H2..H4) ---------------------------------------------
+// dw: the lane's quad (chunk q, row c of the slice); mpq, msq (bw = 4): the pattern bits and sign
+// nibbles of micro-blocks 4q .. 4q + 3, already shifted down; vt: LDS address of this lane's copy
+// of the exchange table; A, sa: the macro-block's digits (this lane's A row and k-group) and their
+// block scale.  P1, P2: this lane group's two digit sums of row c against b1 and b2.
+template <int BW>
+__device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t mpq, uint32_t msq, uint32_t vt,
+                                               const v8i &A, int sa, float &P1, float &P2)
+{
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t dw[4] = {quad.x, quad.y, quad.z, quad.w};
+    v8i B1, B2;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t w = dw[k];
+        uint32_t lo, hi;
+        goq_decode_bytes<BW, 0>(w, lo, hi);                          // H2: code -> E5M2 byte
+        uint32_t eo;                       // LDS address of the entry: vt + 64 * (pattern | signs << 2)
+        if constexpr (BW == 3) {
+            // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
+            // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
+            eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, vt, false);
+        } else {
+            eo = vt + ((((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 6);
+        }
+        const u32x4 ev = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
+        const uint4 e = make_uint4(ev.x, ev.y, ev.z, ev.w);
+        B1[2 * k] = (int)lo;
+        B1[2 * k + 1] = (int)hi;
+        B2[2 * k] = (int)(goq_perm(hi, lo, e.x) ^ e.z);               // H4: exchange + sign XOR
+        B2[2 * k + 1] = (int)(goq_perm(hi, lo, e.y) ^ e.w);
+    }
+    // H3 / H4 accumulate: E5M2 x E5M2, fp32 accumulation; block scale sa on the activation
+    // side, 2^0 on the weight side
+    const v4f D1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B1, zero, 1, 1, 0, sa, 0, 127);
+    const v4f D2 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B2, zero, 1, 1, 0, sa, 0, 127);
+    P1 = D1[0] + D1[1];
+    P2 = D2[0] + D2[1];
+}
+
+// bw = 3 spreads a row's coefficient word over the row's 16 dwords (two bits each): the byte of
+// it that this lane's quad carries
+__device__ __forceinline__ uint32_t coefficient_byte(const uint4 &quad)
+{
+    uint32_t cw = quad.x >> 30;
+    cw = __builtin_amdgcn_alignbit(cw, quad.y, 30);
+    cw = __builtin_amdgcn_alignbit(cw, quad.z, 30);
+    cw = __builtin_amdgcn_alignbit(cw, quad.w, 30);
+    return cw;
+}
+
+// H5: coefficient rescale, once per slab, outside the dot-product loop
+__device__ __forceinline__ float rescale(uint32_t cword, float P1, float P2, float acc)
+{
+    const float c1 = __half2float(__ushort_as_half((unsigned short)(cword & 0xffffu)));
+    const float c2 = __half2float(__ushort_as_half((unsigned short)(cword >> 16)));
+    return fmaf(c2, P2, fmaf(c1, P1, acc));
+}
+
 // ---- one unit of one wavefront: 64 rows x one macro-block (H2..H5) --------------------------
-// buf: the lane's quads; vt: LDS address of this lane's copy of the exchange table; A, sa: the macro-block's digits (this lane's A row
-// and k-group) and their block scale; cwx: this wavefront's 256-byte exchange area for
-// coefficient bytes; acc[j]: running sum of row 16 j + c over the digits this lane receives.
+// buf: the lane's quads; cwx: this wavefront's 256-byte exchange area for coefficient bytes;
+// acc[j]: running sum of row 16 j + c over the digits this lane receives.
 template <int BW>
 __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, uint32_t vt, const v8i &A, int sa,
                                              unsigned char *cwx, int lane, float (&acc)[4])
 {
     const int c = lane & 15, q = lane >> 4;
-    const v4f zero = {0.f, 0.f, 0.f, 0.f};
-    // The coefficient word of row 16 j + c: bw = 3 spreads it over the row's 16 dwords (two bits
-    // each), so the four lanes (c, 0..3) each hold one byte of it; they swap bytes through LDS,
-    // for all four sub-steps at once.  (LDS operations of one wavefront execute in order; the
-    // empty asm only keeps the compiler from moving the reads above the writes.)
+    // The four lanes (c, 0..3) each hold one byte of the coefficient word of row 16 j + c (bw = 3);
+    // they swap bytes through LDS, for all four sub-steps at once.  (LDS operations of one
+    // wavefront execute in order; the empty asm only keeps the compiler from moving the reads
+    // above the writes.)
     if constexpr (BW == 3) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t cw = buf.q[j].x >> 30;
-            cw = __builtin_amdgcn_alignbit(cw, buf.q[j].y, 30);
-            cw = __builtin_amdgcn_alignbit(cw, buf.q[j].z, 30);
-            cw = __builtin_amdgcn_alignbit(cw, buf.q[j].w, 30);
-            cwx[j * 64 + c * 4 + 3 - q] = (unsigned char)cw;
-        }
+        for (int j = 0; j < 4; ++j) cwx[j * 64 + c * 4 + 3 - q] = (unsigned char)coefficient_byte(buf.q[j]);
         asm volatile("" ::: "memory");
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const uint32_t dw[4] = {buf.q[j].x, buf.q[j].y, buf.q[j].z, buf.q[j].w};
         uint32_t mpq = 0, msq = 0;
         if constexpr (BW == 4) {
             mpq = buf.mp[j] >> (8 * q);                      // patterns of micro-blocks 4q .. 4q+3
             msq = buf.ms[j] >> (16 * (q & 1));               // their sign nibbles
         }
-        v8i B1, B2;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t w = dw[k];
-            uint32_t lo, hi;
-            goq_decode_bytes<BW, 0>(w, lo, hi);                          // H2: code -> E5M2 byte
-            uint32_t eo;                       // LDS address of the entry: vt + 64 * (pattern | signs << 2)
-            if constexpr (BW == 3) {
-                // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
-                // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
-                eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, vt, false);
-            } else {
-                eo = vt + ((((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 6);
-            }
-            const u32x4 ev = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
-            const uint4 e = make_uint4(ev.x, ev.y, ev.z, ev.w);
-            B1[2 * k] = (int)lo;
-            B1[2 * k + 1] = (int)hi;
-            B2[2 * k] = (int)(goq_perm(hi, lo, e.x) ^ e.z);               // H4: exchange + sign XOR
-            B2[2 * k + 1] = (int)(goq_perm(hi, lo, e.y) ^ e.w);
-        }
-        // H3 / H4 accumulate: E5M2 x E5M2, fp32 accumulation; block scale sa on the activation
-        // side, 2^0 on the weight side
-        const v4f D1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B1, zero, 1, 1, 0, sa, 0, 127);
-        const v4f D2 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B2, zero, 1, 1, 0, sa, 0, 127);
+        float P1, P2;
+        slice_products<BW>(buf.q[j], mpq, msq, vt, A, sa, P1, P2);
         uint32_t cword;
         if constexpr (BW == 3) cword = *reinterpret_cast<const uint32_t *>(cwx + j * 64 + c * 4);
         else cword = buf.mc[j];
-        // H5: coefficient rescale, once per slab, outside the dot-product loop
-        const float P1 = D1[0] + D1[1];                    // this lane group's two digit sums
-        const float P2 = D2[0] + D2[1];
-        const float c1 = __half2float(__ushort_as_half((unsigned short)(cword & 0xffffu)));
-        const float c2 = __half2float(__ushort_as_half((unsigned short)(cword >> 16)));
-        acc[j] = fmaf(c1, P1, acc[j]);
-        acc[j] = fmaf(c2, P2, acc[j]);
+        acc[j] = rescale(cword, P1, P2, acc[j]);
     }
 }
 
@@ -549,6 +571,142 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
     }
 }
 
+// ---- small layers: one workgroup per 16 output rows ------------------------------------------
+// When a launch has few units per workgroup of the kernel above, each row group is cut among up
+// to gn workgroups and the combine through the scratch area -- a device-scope round trip per
+// batch of contributors -- costs more than the streaming.  This kernel cuts the
+// other way: a workgroup owns 16 output rows (one matrix-instruction tile: sub-step j of row block
+// R) over the whole depth, its eight wavefronts take the macro-blocks round-robin, and the 32
+// partial sums of a row (8 wavefronts x 4 lane groups) meet in LDS, added in a fixed order.  No
+// scratch, no atomics.  Measured against the streaming kernel it is the faster one as long as the
+// grid is small (layers up to about 8192 x 4096 at bw = 3, twice that at bw = 4, whatever the
+// depth); beyond that the streaming kernel's equal pieces win.
+constexpr int RW = NT / 16;              // macro-blocks staged per window: one run per thread
+constexpr int RS = RW / WAVES;           // slices per wavefront and window
+constexpr int ROWS_MAX_TILES[2] = {512, 1024};   // automatic choice: largest grid, bw = 3 | 4
+
+template <int BW>
+struct Slice {
+    uint4 q;
+    uint32_t mp, ms, mc;
+};
+
+template <int BW, int ACT>
+__global__ __launch_bounds__(NT)
+void gemv_rows_kernel(GemvArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + RW * XG];
+    __shared__ __attribute__((aligned(16))) unsigned char stab[RW * 4];
+    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];
+    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256];
+    __shared__ float red[NT];
+    constexpr int CH = (BW == 3) ? 4 : 5;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, q = lane >> 4;
+
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < GOQ_MAX_BATCH; ++i) pi += ((int)blockIdx.x >= a.p[i].bb) ? 1 : 0;   // unused: INT_MAX
+    pi = __builtin_amdgcn_readfirstlane(pi);
+    const GemvProblem &P = a.p[pi];
+    const int lb = (int)blockIdx.x - P.bb;
+    const int R = lb >> 2, j = lb & 3;
+    const int gn = P.gn;
+
+    typedef const __attribute__((address_space(1))) uint32_t *gptr;
+    typedef const __attribute__((address_space(1))) u32x4 *gptr4;
+    gptr rowbase = (gptr)P.packed + (int64_t)R * gn * (CH * GOQ_ROWS * 4) + (16 * j + c) * 4;
+    // slices of macro-blocks w0 + wave + WAVES i (past the end: the last one again, not used)
+    auto request = [&](int w0, Slice<BW> (&s)[RS]) {
+#pragma unroll
+        for (int i = 0; i < RS; ++i) {
+            const int g = min(w0 + wave + WAVES * i, gn - 1);
+            gptr base = rowbase + (int64_t)g * (CH * GOQ_ROWS * 4);
+            const u32x4 v = __builtin_nontemporal_load((gptr4)(base + q * (GOQ_ROWS * 4)));
+            s[i].q = make_uint4(v.x, v.y, v.z, v.w);
+            if constexpr (BW == 4) {
+                gptr pm = base + 4 * (GOQ_ROWS * 4);
+                s[i].mp = __builtin_nontemporal_load(pm);
+                s[i].ms = __builtin_nontemporal_load(pm + 1 + (q >> 1));
+                s[i].mc = __builtin_nontemporal_load(pm + 3);
+            }
+        }
+    };
+    Slice<BW> cur[RS], nxt[RS];
+    request(0, cur);
+
+    for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
+    if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
+
+    // A operand of this lane, as in the kernel above
+    const bool arow_live = (c & 3) < 2;
+    const int digit = 2 * (c >> 2) + (c & 1);
+    const uint32_t abase = arow_live ? (uint32_t)(XZ + q * 256 + digit * 32) : 0u;
+    const uint32_t amask = arow_live ? ~0u : 0u;
+    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane & 3) * 16;
+    unsigned char *cw = cwx + wave * 256;
+
+    float acc = 0.f;
+    for (int w0 = 0; w0 < gn; w0 += RW) {
+        if (w0) __syncthreads();                               // everyone is done with the old window
+        if (tid < min(RW, gn - w0) * 16)
+            stage_run<ACT>(xtab + XZ + (tid >> 4) * XG, stab + (tid >> 4) * 4, P.x, w0 + (tid >> 4), tid & 15);
+        __syncthreads();
+        if (w0 + RW < gn) request(w0 + RW, nxt);
+        if constexpr (BW == 3) {
+#pragma unroll
+            for (int i = 0; i < RS; ++i) cw[i * 64 + c * 4 + 3 - q] = (unsigned char)coefficient_byte(cur[i].q);
+            asm volatile("" ::: "memory");
+        }
+#pragma unroll
+        for (int i = 0; i < RS; ++i) {
+            const int slot = wave + WAVES * i;
+            if (w0 + slot < gn) {
+                const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
+                const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
+                const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * digit;
+                uint32_t mpq = 0, msq = 0;
+                if constexpr (BW == 4) {
+                    mpq = cur[i].mp >> (8 * q);
+                    msq = cur[i].ms >> (16 * (q & 1));
+                }
+                float P1, P2;
+                slice_products<BW>(cur[i].q, mpq, msq, vt_lane, A, sa, P1, P2);
+                uint32_t cword;
+                if constexpr (BW == 3) cword = *reinterpret_cast<const uint32_t *>(cw + i * 64 + c * 4);
+                else cword = cur[i].mc;
+                acc = rescale(cword, P1, P2, acc);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < RS; ++i) cur[i] = nxt[i];
+    }
+    // H6: the 32 partial sums of row c, in wavefront and lane-group order
+    red[tid] = acc;
+    __syncthreads();
+    if (tid < 16) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NT / 16; ++i) s += red[i * 16 + tid];
+        if constexpr (ACT != 0) s *= P.sx[0];
+        const int row = R * GOQ_ROWS + 16 * j + tid;
+        if (row < P.out) {
+            if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row] = s;
+            else reinterpret_cast<__half *>(P.y)[row] = __float2half(s);
+        }
+    }
+}
+
+template <int BW, int ACT>
+int launch_rows(hipStream_t st, const GemvArgs &a, int nblocks)
+{
+    hipLaunchKernelGGL((gemv_rows_kernel<BW, ACT>), dim3(nblocks), dim3(NT), 0, st, a);
+    return goq_check_launch("goq_gemv");
+}
+
 template <int BW, int ACT>
 int launch(hipStream_t st, const GemvArgs &a, int nwg)
 {
@@ -575,7 +733,11 @@ Region *scratch_base()
     return p;
 }
 
+std::atomic<int> g_kernel{GOQ_GEMV_AUTO};
+
 }  // namespace
+
+void goq_gemv_set_kernel(int kernel) { g_kernel.store(kernel, std::memory_order_relaxed); }
 
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs)
 {
@@ -599,6 +761,27 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     }
     for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].begin = 0x7fffffff; }
     a.total = (int)total;
+    // Small launches go to the row-owner kernel: one workgroup per 16 output rows.
+    {
+        int64_t blocks = 0;
+        for (int i = 0; i < n; ++i) {
+            a.p[i].bb = (int)blocks;
+            blocks += (descs[i].out + 15) / 16;
+        }
+        for (int i = n; i < GOQ_MAX_BATCH; ++i) a.p[i].bb = 0x7fffffff;
+        const int which = g_kernel.load(std::memory_order_relaxed);
+        if (blocks > 0x3fffffff) return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
+        if (which == GOQ_GEMV_ROWS ||
+            (which == GOQ_GEMV_AUTO && blocks <= ROWS_MAX_TILES[bw == 4])) {
+            const int nb = (int)blocks;
+            if (bw == 3 && act == GOQ_A16) return launch_rows<3, 0>(st, a, nb);
+            if (bw == 3 && act == GOQ_A8) return launch_rows<3, 1>(st, a, nb);
+            if (bw == 4 && act == GOQ_A8) return launch_rows<4, 1>(st, a, nb);
+            if (bw == 3 && act == GOQ_A4) return launch_rows<3, 2>(st, a, nb);
+            if (bw == 4 && act == GOQ_A4) return launch_rows<4, 2>(st, a, nb);
+            return launch_rows<4, 0>(st, a, nb);
+        }
+    }
     // Scratch for row groups cut by a piece boundary.  Launches take the regions round-robin, so
     // up to REGIONS launches may be in flight (on different streams) without sharing one.
     static std::atomic<unsigned> ticket{0};

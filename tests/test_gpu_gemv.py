@@ -6,7 +6,10 @@ the denominator floored at 1 % of the output rms, and normalised backward error
 backward error is additionally held to 2e-6: the GEMV hands x to the matrix instruction as block
 fixed point with 24 bits below each 32-activation block's maximum, products are exact, sums are
 fp32.  A8: the slab partials are exact integers by construction; y is held to 1e-5
-normalised error against the fp64 oracle."""
+normalised error against the fp64 oracle.
+
+The library has two batch-1 kernels (streaming and row-owner) and picks by size; the parity cases
+run under each of them, forced through goq_gemv_select, and under the automatic choice."""
 import numpy as np
 import pytest
 
@@ -16,6 +19,18 @@ from tests import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-3
+KERNELS = ["AUTO", "STREAM", "ROWS"]
+
+
+@pytest.fixture(autouse=True)
+def _automatic_kernel_choice_after_each_test():
+    yield
+    import paper_2605_26092_amd as goq
+    goq.gemv_select(goq.GEMV_AUTO)
+
+
+def _select(goq, kernel):
+    goq.gemv_select(getattr(goq, "GEMV_" + kernel))
 
 
 def _quantize(oracle, bw, out, inn, cid):
@@ -37,35 +52,42 @@ def _run_gemv(goq, q, x_np, act, ytype, sx_np=None):
 
 @pytest.mark.parametrize("bw", [3, 4])
 @pytest.mark.parametrize("ytype_name", ["F32", "F16"])
-@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (3, 256), (17, 384), (200, 512), (1100, 1024), (600, 4096)])
+@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (3, 256), (17, 384), (200, 512), (1100, 1024), (600, 4096),
+                                   (150, 6400), (8300, 256)])
 def test_gemv_a16_small(oracle, bw, ytype_name, shape):
+    """(8300, 256) has more 16-row tiles than the automatic choice gives the row-owner kernel at
+    bw = 3; 6400 = 50 macro-blocks spans two of that kernel's staging windows."""
     import paper_2605_26092_amd as goq
     out, inn = shape
-    print("gemv a16 bw=%d %s out=%d in=%d" % (bw, ytype_name, out, inn), flush=True)
     q = _quantize(oracle, bw, out, inn, 31)
     x = goq_inputs.activations_a16(1, inn, config_id=31, tensor_id=100 + out, outlier_frac=0.01)
     ref = oracle.gemm_a16(q, x, threads=8)[0]
-    y = _run_gemv(goq, q, x, goq.A16, getattr(goq, ytype_name))
     what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
-    e1, e2 = gu.a16_errors(y, ref, x[0], what_abs)
-    assert e1 <= TOL and e2 <= TOL, (e1, e2)
-    if ytype_name == "F32":
-        assert e2 <= 2e-6, e2
+    for kernel in KERNELS:
+        print("gemv a16 bw=%d %s out=%d in=%d kernel=%s" % (bw, ytype_name, out, inn, kernel), flush=True)
+        _select(goq, kernel)
+        y = _run_gemv(goq, q, x, goq.A16, getattr(goq, ytype_name))
+        e1, e2 = gu.a16_errors(y, ref, x[0], what_abs)
+        assert e1 <= TOL and e2 <= TOL, (kernel, e1, e2)
+        if ytype_name == "F32":
+            assert e2 <= 2e-6, (kernel, e2)
 
 
 @pytest.mark.parametrize("bw", [3, 4])
-@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (17, 384), (200, 768), (1100, 1024)])
+@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (17, 384), (200, 768), (1100, 1024), (150, 6400)])
 def test_gemv_a8(oracle, bw, shape):
     import paper_2605_26092_amd as goq
     out, inn = shape
-    print("gemv a8 bw=%d out=%d in=%d" % (bw, out, inn), flush=True)
     q = _quantize(oracle, bw, out, inn, 32)
     xq, sx = goq_inputs.activations_a8(1, inn, config_id=32, tensor_id=200 + out)
     ref, _ = oracle.gemm_a8(q, xq, sx, threads=8)
-    y = _run_gemv(goq, q, xq, goq.A8, goq.F32, sx_np=sx)
     what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
     scale = (np.abs(xq[0].astype(np.float64)) * float(sx[0])) @ what_abs.T
-    assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5
+    for kernel in KERNELS:
+        print("gemv a8 bw=%d out=%d in=%d kernel=%s" % (bw, out, inn, kernel), flush=True)
+        _select(goq, kernel)
+        y = _run_gemv(goq, q, xq, goq.A8, goq.F32, sx_np=sx)
+        assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5, kernel
 
 
 @pytest.mark.parametrize("bw", [3, 4])
@@ -80,15 +102,19 @@ def test_gemv_a4(oracle, bw, shape):
     xq, sx = goq_inputs.activations_int(1, inn, 4, config_id=34, tensor_id=200 + out)
     xq[0, :8] = [-8, 7, -7, 0, 1, -1, -8, 7]               # the full nibble range incl. -8
     ref, _ = oracle.gemm_a8(q, xq, sx, threads=8)
-    y = _run_gemv(goq, q, goq_inputs.pack_int4(xq), goq.A4, goq.F32, sx_np=sx)
     what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
     scale = (np.abs(xq[0].astype(np.float64)) * float(sx[0])) @ what_abs.T
-    assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5
+    for kernel in KERNELS:
+        _select(goq, kernel)
+        y = _run_gemv(goq, q, goq_inputs.pack_int4(xq), goq.A4, goq.F32, sx_np=sx)
+        assert np.max(np.abs(y - ref[0]) / scale) <= 1e-5, kernel
 
 
-def test_gemv_edge_cases(oracle):
+@pytest.mark.parametrize("kernel", ["STREAM", "ROWS"])
+def test_gemv_edge_cases(oracle, kernel):
     """all-zero codes, extreme fp16 activations, int8 saturation, single basis (c2 = 0)."""
     import paper_2605_26092_amd as goq
+    _select(goq, kernel)
     q = goq_inputs.canonical_random(3, 130, 256, config_id=33)
     q["codes"][:64] = 3                                   # zero state everywhere in the first 64 rows
     q["c2"][64:100] = 0                                   # K = 1 rows
@@ -118,9 +144,11 @@ def test_gemv_edge_cases(oracle):
     assert np.allclose(yr, xs.astype(np.float64).sum(), rtol=1e-5)
 
 
-def test_gemv_batch_matches_single_calls(oracle):
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_gemv_batch_matches_single_calls(oracle, kernel):
     import paper_2605_26092_amd as goq
     torch = gu.torch_cuda()
+    _select(goq, kernel)
     shapes = [(256, 512), (1100, 512), (200, 1024)]
     probs, refs, ys = [], [], []
     keep = []
@@ -149,10 +177,12 @@ def test_gemv_config1_full_size(oracle, bw):
     q = _quantize(oracle, bw, 4096, 4096, 0)
     x = goq_inputs.activations_a16(1, 4096, config_id=0, tensor_id=100)
     ref = oracle.gemm_a16(q, x, threads=8)[0]
-    for ytype in (goq.F32, goq.F16):
-        y = _run_gemv(goq, q, x, goq.A16, ytype)
-        e1, _ = gu.a16_errors(y, ref, None)
-        assert e1 <= TOL, (ytype, e1)
+    for kernel in KERNELS:                                 # the automatic choice here is ROWS
+        _select(goq, kernel)
+        for ytype in (goq.F32, goq.F16):
+            y = _run_gemv(goq, q, x, goq.A16, ytype)
+            e1, _ = gu.a16_errors(y, ref, None)
+            assert e1 <= TOL, (kernel, ytype, e1)
 
 
 def test_gemv_two_streams_in_flight_and_repeatable(oracle):
@@ -161,6 +191,7 @@ def test_gemv_two_streams_in_flight_and_repeatable(oracle):
     must all give the single-launch result, bit for bit (the combine order is fixed)."""
     import paper_2605_26092_amd as goq
     torch = gu.torch_cuda()
+    goq.gemv_select(goq.GEMV_STREAM)
     layers = []
     for i, (out, inn) in enumerate([(1500, 2048), (700, 4096)]):
         q = _quantize(oracle, 3, out, inn, 36 + i)
