@@ -149,9 +149,10 @@ def bench_gemv(args, shapes, bw, name):
 
 def gemv_kernel_name(bw, shapes):
     """The kernel the library's automatic choice launches for these layers (see goq_gemv_select in
-    include/goq.h): the row-owner kernel up to 512 (bw = 3) or 1024 (bw = 4) 16-row tiles."""
+    include/goq.h): the row-owner kernel up to 512 16-row tiles and 24576 (tile, macro-block) pairs."""
     tiles = sum((out + 15) // 16 for _, out, _ in shapes)
-    return ("gemv_rows_kernel<%d,0>" if tiles <= (512 if bw == 3 else 1024) else "gemv_kernel<%d,0>") % bw
+    slices = sum((out + 15) // 16 * (inn // 128) for _, out, inn in shapes)
+    return ("gemv_rows_kernel<%d,0>" if tiles <= 512 and slices <= 24576 else "gemv_kernel<%d,0>") % bw
 
 
 def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):

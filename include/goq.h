@@ -137,9 +137,9 @@ int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *de
 /* Which of the two batch-1 kernels goq_gemv / goq_gemv_batch launch (process-wide, takes effect
  * with the next call; both kernels compute the same sums, H2..H6 of Sec. 3.3, and both accept
  * every shape):
- *   GOQ_GEMV_AUTO   (default) by size: launches of at most 8192 (bw = 3) or 16384 (bw = 4)
- *                   output rows in all, each problem's rows rounded up to 16, go to the
- *                   row-owner kernel, everything else streams;
+ *   GOQ_GEMV_AUTO   (default) by size: launches of at most 512 tiles of 16 output rows (each
+ *                   problem's rows rounded up to 16) and at most 24576 (tile, macro-block)
+ *                   pairs -- 48 Mi weights -- go to the row-owner kernel, everything else streams;
  *   GOQ_GEMV_STREAM the streaming kernel: equal contiguous pieces of the launch's weight bytes
  *                   per workgroup, split row groups combined through the scratch area;
  *   GOQ_GEMV_ROWS   the row-owner kernel: one workgroup per 16 output rows over the whole depth,

@@ -57,22 +57,20 @@ __device__ __forceinline__ void goq_decode_bytes(uint32_t w, uint32_t &lo, uint3
         hi = goq_perm(GoqLut<3, ACT>::hi, GoqLut<3, ACT>::lo, chi);
     } else {
         static_assert(ACT == 0, "bw = 4 with int8 activations: b * 128 does not fit int8");
-        // nibble = sign << 3 | e ; fp16 high byte = sign << 7 | (15 - e) << 2 ; (0, 7) -> 0x00
-        const uint32_t nlo = w & 0x0F0F0F0Fu;
-        const uint32_t nhi = (w >> 4) & 0x0F0F0F0Fu;
+        // nibble = sign << 3 | e ; fp16 high byte = sign << 7 | (15 - e) << 2 ; (0, 7) -> 0x00.
+        // Both lattice halves are looked up by e; a third permute picks per byte by the sign bit
+        // (selector byte i = i for the positive, 4 + i for the negative look-up).
         constexpr uint32_t PL = 0x3034383Cu, PH = 0x0024282Cu;   // +2^0 .. +2^-6, zero
         constexpr uint32_t NL = 0xB0B4B8BCu, NH = 0xA0A4A8ACu;   // -2^0 .. -2^-7
         {
-            const uint32_t e = nlo & 0x07070707u, s = (nlo >> 3) & 0x01010101u;
-            const uint32_t m = (s << 8) - s;                      // 0xFF in every negative byte
-            const uint32_t p = goq_perm(PH, PL, e), n = goq_perm(NH, NL, e);
-            lo = (n & m) | (p & ~m);
+            const uint32_t e = w & 0x07070707u;
+            const uint32_t pick = ((w >> 1) & 0x04040404u) | 0x03020100u;
+            lo = goq_perm(goq_perm(NH, NL, e), goq_perm(PH, PL, e), pick);
         }
         {
-            const uint32_t e = nhi & 0x07070707u, s = (nhi >> 3) & 0x01010101u;
-            const uint32_t m = (s << 8) - s;
-            const uint32_t p = goq_perm(PH, PL, e), n = goq_perm(NH, NL, e);
-            hi = (n & m) | (p & ~m);
+            const uint32_t e = (w >> 4) & 0x07070707u;
+            const uint32_t pick = ((w >> 5) & 0x04040404u) | 0x03020100u;
+            hi = goq_perm(goq_perm(NH, NL, e), goq_perm(PH, PL, e), pick);
         }
     }
 }

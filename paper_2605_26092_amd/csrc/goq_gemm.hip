@@ -100,9 +100,9 @@ __device__ __forceinline__ uint32_t exchange_address(uint32_t w, const uint4 &me
         const uint32_t u = __umul24(w & 0x00C0C0C0u, 0x1041u);
         return vt + ((u >> 14) & 0x3F0u);
     } else {
-        const uint32_t pat = (meta.x >> (2 * m)) & 3u;
-        const uint32_t sg = (meta.y >> (4 * (m & 7))) & 15u;   // meta.y already holds this lane's half
-        return vt + ((pat | (sg << 2)) << 4);
+        // meta.x, meta.y: the metadata dwords of this lane's two chunks (6 bits per micro-block)
+        const uint32_t md = m < 4 ? meta.x : meta.y;
+        return vt + (((md >> (6 * (m & 3))) & 63u) << 4);
     }
 }
 
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
 
     struct Weights {
         uint4 q0, q1;     // micro-blocks 8 kg .. 8 kg + 3 and 8 kg + 4 .. 8 kg + 7
-        uint4 meta;       // bw = 4: patterns and sign nibbles of these micro-blocks, coefficient word
+        uint4 meta;       // bw = 4: metadata dwords of the two chunks (x, y), coefficient word (w)
     };
     auto load_weights = [&](int g, Weights &w) {
         const uint32_t *p = wq + g * gstride;
@@ -203,9 +203,11 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
         w.q1 = *reinterpret_cast<const uint4 *>(p + GOQ_ROWS * 4);
         w.meta = make_uint4(0, 0, 0, 0);
         if constexpr (BW == 4) {
-            // chunk 4 of the same row: patterns, signs of m = 0..7, signs of m = 8..15, coefficient word
+            // chunk 4 of the same row: one metadata dword per chunk, each with a byte of the
+            // coefficient word on top
             const uint4 mq = *reinterpret_cast<const uint4 *>(p + (4 - 2 * kg) * GOQ_ROWS * 4);
-            w.meta = make_uint4(mq.x >> (16 * kg), kg ? mq.z : mq.y, 0, mq.w);
+            const uint32_t cw = goq_perm(mq.y, mq.x, 0x0c0c0703u) | goq_perm(mq.w, mq.z, 0x07030c0cu);
+            w.meta = make_uint4(kg ? mq.z : mq.x, kg ? mq.w : mq.y, 0, cw);
         }
     };
     auto word_of = [](const Weights &w, int t) {

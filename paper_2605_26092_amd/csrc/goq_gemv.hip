@@ -119,12 +119,11 @@ __device__ __forceinline__ uint4 exchange_entry(int v)
 }
 
 // What one lane holds of one unit: for j = 0..3 the quad (chunk q, row 16 j + c); for bw = 4
-// also, of row 16 j + c, the pattern word, the half of the sign words that covers chunk q, and
-// the coefficient word.
+// also the metadata dword of chunk q of that row.
 template <int BW>
 struct UnitBuf {
     uint4 q[4];
-    uint32_t mp[(BW == 4) ? 4 : 1], ms[(BW == 4) ? 4 : 1], mc[(BW == 4) ? 4 : 1];
+    uint32_t md[(BW == 4) ? 4 : 1];
 };
 
 template <int BW>
@@ -145,13 +144,9 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ packed, i
         u.q[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
     if constexpr (BW == 4) {
-        gptr pm = base + 4 * (GOQ_ROWS * 4) + c * 4;
+        gptr pm = base + 4 * (GOQ_ROWS * 4) + c * 4 + q;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            u.mp[j] = __builtin_nontemporal_load(pm + 64 * j);
-            u.ms[j] = __builtin_nontemporal_load(pm + 64 * j + 1 + (q >> 1));
-            u.mc[j] = __builtin_nontemporal_load(pm + 64 * j + 3);
-        }
+        for (int j = 0; j < 4; ++j) u.md[j] = __builtin_nontemporal_load(pm + 64 * j);
     }
 }
 
@@ -293,12 +288,11 @@ __device__ __forceinline__ void stage_window(const GemvArgs &a, int u0, int ns, 
 }
 
 // ---- one 16-row slice of a macro-block (H2..H4) ---------------------------------------------
-// dw: the lane's quad (chunk q, row c of the slice); mpq, msq (bw = 4): the pattern bits and sign
-// nibbles of micro-blocks 4q .. 4q + 3, already shifted down; vt: LDS address of this lane's copy
-// of the exchange table; A, sa: the macro-block's digits (this lane's A row and k-group) and their
+// quad: the lane's quad (chunk q, row c of the slice); md (bw = 4): the metadata dword of that
+// chunk and row; vt: LDS address of this lane's copy of the exchange table; A, sa: the macro-block's digits (this lane's A row and k-group) and their
 // block scale.  P1, P2: this lane group's two digit sums of row c against b1 and b2.
 template <int BW>
-__device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t mpq, uint32_t msq, uint32_t vt,
+__device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t md, uint32_t vt,
                                                const v8i &A, int sa, float &P1, float &P2)
 {
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
@@ -315,7 +309,7 @@ __device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t mpq, 
             // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
             eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, vt, false);
         } else {
-            eo = vt + ((((mpq >> (2 * k)) & 3u) | (((msq >> (4 * k)) & 15u) << 2)) << 6);
+            eo = vt + (((md >> (6 * k)) & 63u) << 6);
         }
         const u32x4 ev = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
         const uint4 e = make_uint4(ev.x, ev.y, ev.z, ev.w);
@@ -332,16 +326,24 @@ __device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t mpq, 
     P2 = D2[0] + D2[1];
 }
 
-// bw = 3 spreads a row's coefficient word over the row's 16 dwords (two bits each): the byte of
-// it that this lane's quad carries
-__device__ __forceinline__ uint32_t coefficient_byte(const uint4 &quad)
+// A row's coefficient word is spread over what its four lanes (c, 0..3) load, one byte each: two
+// bits in each of the quad's dwords (bw = 3), the top byte of the metadata dword (bw = 4).
+// position: the byte of the word this lane holds.
+template <int BW>
+__device__ __forceinline__ uint32_t coefficient_byte(const uint4 &quad, uint32_t md)
 {
-    uint32_t cw = quad.x >> 30;
-    cw = __builtin_amdgcn_alignbit(cw, quad.y, 30);
-    cw = __builtin_amdgcn_alignbit(cw, quad.z, 30);
-    cw = __builtin_amdgcn_alignbit(cw, quad.w, 30);
-    return cw;
+    if constexpr (BW == 3) {
+        uint32_t cw = quad.x >> 30;
+        cw = __builtin_amdgcn_alignbit(cw, quad.y, 30);
+        cw = __builtin_amdgcn_alignbit(cw, quad.z, 30);
+        cw = __builtin_amdgcn_alignbit(cw, quad.w, 30);
+        return cw;
+    } else {
+        return md >> 24;
+    }
 }
+template <int BW>
+__device__ __forceinline__ int coefficient_byte_position(int q) { return BW == 3 ? 3 - q : q; }
 
 // H5: coefficient rescale, once per slab, outside the dot-product loop
 __device__ __forceinline__ float rescale(uint32_t cword, float P1, float P2, float acc)
@@ -359,27 +361,20 @@ __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, uint32_t vt
                                              unsigned char *cwx, int lane, float (&acc)[4])
 {
     const int c = lane & 15, q = lane >> 4;
-    // The four lanes (c, 0..3) each hold one byte of the coefficient word of row 16 j + c (bw = 3);
-    // they swap bytes through LDS, for all four sub-steps at once.  (LDS operations of one
-    // wavefront execute in order; the empty asm only keeps the compiler from moving the reads
-    // above the writes.)
-    if constexpr (BW == 3) {
+    // The four lanes (c, 0..3) each hold one byte of the coefficient word of row 16 j + c; they
+    // swap bytes through LDS, for all four sub-steps at once.  (LDS operations of one wavefront
+    // execute in order; the empty asm only keeps the compiler from moving the reads above the
+    // writes.)
+    const int cpos = coefficient_byte_position<BW>(q);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) cwx[j * 64 + c * 4 + 3 - q] = (unsigned char)coefficient_byte(buf.q[j]);
-        asm volatile("" ::: "memory");
-    }
+    for (int j = 0; j < 4; ++j)
+        cwx[j * 64 + c * 4 + cpos] = (unsigned char)coefficient_byte<BW>(buf.q[j], buf.md[BW == 4 ? j : 0]);
+    asm volatile("" ::: "memory");
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        uint32_t mpq = 0, msq = 0;
-        if constexpr (BW == 4) {
-            mpq = buf.mp[j] >> (8 * q);                      // patterns of micro-blocks 4q .. 4q+3
-            msq = buf.ms[j] >> (16 * (q & 1));               // their sign nibbles
-        }
         float P1, P2;
-        slice_products<BW>(buf.q[j], mpq, msq, vt, A, sa, P1, P2);
-        uint32_t cword;
-        if constexpr (BW == 3) cword = *reinterpret_cast<const uint32_t *>(cwx + j * 64 + c * 4);
-        else cword = buf.mc[j];
+        slice_products<BW>(buf.q[j], buf.md[BW == 4 ? j : 0], vt, A, sa, P1, P2);
+        const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + j * 64 + c * 4);
         acc[j] = rescale(cword, P1, P2, acc[j]);
     }
 }
@@ -579,16 +574,16 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
 // R) over the whole depth, its eight wavefronts take the macro-blocks round-robin, and the 32
 // partial sums of a row (8 wavefronts x 4 lane groups) meet in LDS, added in a fixed order.  No
 // scratch, no atomics.  Measured against the streaming kernel it is the faster one as long as the
-// grid is small (layers up to about 8192 x 4096 at bw = 3, twice that at bw = 4, whatever the
-// depth); beyond that the streaming kernel's equal pieces win.
+// grid fits the chip in one go and the launch is small (layers up to about 8192 x 4096 or
+// 4096 x 11008); beyond that the streaming kernel's equal pieces win.
 constexpr int RW = NT / 16;              // macro-blocks staged per window: one run per thread
 constexpr int RS = RW / WAVES;           // slices per wavefront and window
-constexpr int ROWS_MAX_TILES[2] = {512, 1024};   // automatic choice: largest grid, bw = 3 | 4
+constexpr int ROWS_MAX_TILES = 512;      // automatic choice: largest grid ...
+constexpr int ROWS_MAX_SLICES = 24576;   // ... and most (tile, macro-block) slices per launch
 
-template <int BW>
 struct Slice {
     uint4 q;
-    uint32_t mp, ms, mc;
+    uint32_t md;
 };
 
 template <int BW, int ACT>
@@ -620,22 +615,18 @@ void gemv_rows_kernel(GemvArgs a)
     typedef const __attribute__((address_space(1))) u32x4 *gptr4;
     gptr rowbase = (gptr)P.packed + (int64_t)R * gn * (CH * GOQ_ROWS * 4) + (16 * j + c) * 4;
     // slices of macro-blocks w0 + wave + WAVES i (past the end: the last one again, not used)
-    auto request = [&](int w0, Slice<BW> (&s)[RS]) {
+    auto request = [&](int w0, Slice (&s)[RS]) {
 #pragma unroll
         for (int i = 0; i < RS; ++i) {
             const int g = min(w0 + wave + WAVES * i, gn - 1);
             gptr base = rowbase + (int64_t)g * (CH * GOQ_ROWS * 4);
             const u32x4 v = __builtin_nontemporal_load((gptr4)(base + q * (GOQ_ROWS * 4)));
             s[i].q = make_uint4(v.x, v.y, v.z, v.w);
-            if constexpr (BW == 4) {
-                gptr pm = base + 4 * (GOQ_ROWS * 4);
-                s[i].mp = __builtin_nontemporal_load(pm);
-                s[i].ms = __builtin_nontemporal_load(pm + 1 + (q >> 1));
-                s[i].mc = __builtin_nontemporal_load(pm + 3);
-            }
+            s[i].md = 0u;
+            if constexpr (BW == 4) s[i].md = __builtin_nontemporal_load(base + 4 * (GOQ_ROWS * 4) + q);
         }
     };
-    Slice<BW> cur[RS], nxt[RS];
+    Slice cur[RS], nxt[RS];
     request(0, cur);
 
     for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
@@ -656,11 +647,10 @@ void gemv_rows_kernel(GemvArgs a)
             stage_run<ACT>(xtab + XZ + (tid >> 4) * XG, stab + (tid >> 4) * 4, P.x, w0 + (tid >> 4), tid & 15);
         __syncthreads();
         if (w0 + RW < gn) request(w0 + RW, nxt);
-        if constexpr (BW == 3) {
 #pragma unroll
-            for (int i = 0; i < RS; ++i) cw[i * 64 + c * 4 + 3 - q] = (unsigned char)coefficient_byte(cur[i].q);
-            asm volatile("" ::: "memory");
-        }
+        for (int i = 0; i < RS; ++i)
+            cw[i * 64 + c * 4 + coefficient_byte_position<BW>(q)] = (unsigned char)coefficient_byte<BW>(cur[i].q, cur[i].md);
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int i = 0; i < RS; ++i) {
             const int slot = wave + WAVES * i;
@@ -668,17 +658,9 @@ void gemv_rows_kernel(GemvArgs a)
                 const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
                 const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
                 const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * digit;
-                uint32_t mpq = 0, msq = 0;
-                if constexpr (BW == 4) {
-                    mpq = cur[i].mp >> (8 * q);
-                    msq = cur[i].ms >> (16 * (q & 1));
-                }
                 float P1, P2;
-                slice_products<BW>(cur[i].q, mpq, msq, vt_lane, A, sa, P1, P2);
-                uint32_t cword;
-                if constexpr (BW == 3) cword = *reinterpret_cast<const uint32_t *>(cw + i * 64 + c * 4);
-                else cword = cur[i].mc;
-                acc = rescale(cword, P1, P2, acc);
+                slice_products<BW>(cur[i].q, cur[i].md, vt_lane, A, sa, P1, P2);
+                acc = rescale(*reinterpret_cast<const uint32_t *>(cw + i * 64 + c * 4), P1, P2, acc);
             }
         }
 #pragma unroll
@@ -763,16 +745,17 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     a.total = (int)total;
     // Small launches go to the row-owner kernel: one workgroup per 16 output rows.
     {
-        int64_t blocks = 0;
+        int64_t blocks = 0, slices = 0;
         for (int i = 0; i < n; ++i) {
             a.p[i].bb = (int)blocks;
             blocks += (descs[i].out + 15) / 16;
+            slices += (descs[i].out + 15) / 16 * a.p[i].gn;
         }
         for (int i = n; i < GOQ_MAX_BATCH; ++i) a.p[i].bb = 0x7fffffff;
         const int which = g_kernel.load(std::memory_order_relaxed);
         if (blocks > 0x3fffffff) return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
         if (which == GOQ_GEMV_ROWS ||
-            (which == GOQ_GEMV_AUTO && blocks <= ROWS_MAX_TILES[bw == 4])) {
+            (which == GOQ_GEMV_AUTO && blocks <= ROWS_MAX_TILES && slices <= ROWS_MAX_SLICES)) {
             const int nb = (int)blocks;
             if (bw == 3 && act == GOQ_A16) return launch_rows<3, 0>(st, a, nb);
             if (bw == 3 && act == GOQ_A8) return launch_rows<3, 1>(st, a, nb);

@@ -19,9 +19,10 @@
 //   bits (31-2m, 30-2m): folding cw = (cw << 2) | (dword >> 30) over m = 0..15 rebuilds CW.
 //
 // bw = 4 (CH = 5, 80 B per macro-block row = 5.0 bit/weight): chunks 0..3 as above but a dword
-//   is eight 4-bit codes, byte j = code[8m+j] | code[8m+j+4] << 4.  Chunk 4 holds
-//   dword 0 = patterns (2 bits at 2m), dword 1 = signs of m = 0..7 (4 bits at 4m),
-//   dword 2 = signs of m = 8..15, dword 3 = CW.
+//   is eight 4-bit codes, byte j = code[8m+j] | code[8m+j+4] << 4.  Chunk 4 holds the metadata,
+//   dword q for the four micro-blocks of chunk q: bits 6i..6i+5 = pattern | signs << 2 of
+//   micro-block m = 4q + i (i = 0..3), bits 24..31 = byte q of CW.  The lane that decodes chunk q
+//   of a row thus needs this one dword besides its quad.
 //
 // Rows are padded to a multiple of 64 with zero-valued codes and zero coefficients.
 #pragma once

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void pack_kernel(int64_t out, int64_t in,
     const uint8_t *pp = pattern + (row * in + g * GOQ_N) / GOQ_G;
     const uint8_t *sp = signs + (row * in + g * GOQ_N) / GOQ_G;
 
-    uint32_t meta_pat = 0, meta_s0 = 0, meta_s1 = 0;
+    uint32_t meta[4] = {0, 0, 0, 0};
     for (int h = 0; h < 4; ++h) {
         uint32_t d[4];
         for (int q = 0; q < 4; ++q) {
@@ -56,9 +56,7 @@ __global__ __launch_bounds__(256) void pack_kernel(int64_t out, int64_t in,
                 w |= (sg >> 2) << 22;
                 w |= ((cw >> (30 - 2 * m)) & 3u) << 30;
             } else {
-                meta_pat |= pat << (2 * m);
-                if (m < 8) meta_s0 |= sg << (4 * m);
-                else meta_s1 |= sg << (4 * (m - 8));
+                meta[h] |= (pat | (sg << 2)) << (6 * q);
             }
             d[q] = w;
         }
@@ -67,7 +65,8 @@ __global__ __launch_bounds__(256) void pack_kernel(int64_t out, int64_t in,
     }
     if (BW == 4) {
         uint4 *dst = reinterpret_cast<uint4 *>(packed + goq_quad_index(CH, gn, R, g, 4, r));
-        *dst = make_uint4(meta_pat, meta_s0, meta_s1, cw);
+        for (int h = 0; h < 4; ++h) meta[h] |= ((cw >> (8 * h)) & 0xffu) << 24;
+        *dst = make_uint4(meta[0], meta[1], meta[2], meta[3]);
     }
 }
 
@@ -118,12 +117,14 @@ __global__ __launch_bounds__(256) void unpack_kernel(int64_t out, int64_t in,
                 sp[m] = (uint8_t)(((w >> 14) & 3u) | (((w >> 22) & 3u) << 2));
                 cw = (cw << 2) | (w >> 30);
             } else {
-                pp[m] = (uint8_t)((meta.x >> (2 * m)) & 3u);
-                sp[m] = (uint8_t)(((m < 8 ? meta.y >> (4 * m) : meta.z >> (4 * (m - 8)))) & 15u);
+                const uint32_t md = h == 0 ? meta.x : h == 1 ? meta.y : h == 2 ? meta.z : meta.w;
+                const uint32_t v = (md >> (6 * q)) & 63u;
+                pp[m] = (uint8_t)(v & 3u);
+                sp[m] = (uint8_t)(v >> 2);
             }
         }
     }
-    if (BW == 4) cw = meta.w;
+    if (BW == 4) cw = (meta.x >> 24) | ((meta.y >> 24) << 8) | ((meta.z >> 24) << 16) | ((meta.w >> 24) << 24);
     c1[row * gn + g] = (uint16_t)(cw & 0xffffu);
     c2[row * gn + g] = (uint16_t)(cw >> 16);
 }

@@ -55,8 +55,8 @@ def _run_gemv(goq, q, x_np, act, ytype, sx_np=None):
 @pytest.mark.parametrize("shape", [(1, 128), (64, 128), (3, 256), (17, 384), (200, 512), (1100, 1024), (600, 4096),
                                    (150, 6400), (8300, 256)])
 def test_gemv_a16_small(oracle, bw, ytype_name, shape):
-    """(8300, 256) has more 16-row tiles than the automatic choice gives the row-owner kernel at
-    bw = 3; 6400 = 50 macro-blocks spans two of that kernel's staging windows."""
+    """(8300, 256) has more 16-row tiles than the automatic choice gives the row-owner kernel;
+    6400 = 50 macro-blocks spans two of that kernel's staging windows."""
     import paper_2605_26092_amd as goq
     out, inn = shape
     q = _quantize(oracle, bw, out, inn, 31)
