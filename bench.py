@@ -155,9 +155,11 @@ def gemv_kernel_name(bw, shapes):
     return ("gemv_rows_kernel<%d,0>" if tiles <= 512 and slices <= 24576 else "gemv_kernel<%d,0>") % bw
 
 
-def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
+def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, folded=False):
     """The same block as many-token GEMMs (one launch per matrix): issued ops = 4 M N K (two PoT
-    bases), dense-equivalent = 2 M N K.  Reported next to the headline, not instead of it."""
+    bases), dense-equivalent = 2 M N K.  Reported next to the headline, not instead of it.
+    folded: the ablation goq_gemm_folded (one contraction with the fp16 weight c1 b1 + c2 b2):
+    issued = dense-equivalent = 2 M N K."""
     import torch
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")
@@ -179,7 +181,10 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
 
     def step():
         for k, (_, out, inn) in enumerate(shapes):
-            goq.gemm(bw, act, tokens, out, inn, packed[k], Xs[k], sxs[k], Ys[k], goq.F16, stream=stream)
+            if folded:
+                goq.gemm_folded(bw, tokens, out, inn, packed[k], Xs[k], Ys[k], goq.F16, stream=stream)
+            else:
+                goq.gemm(bw, act, tokens, out, inn, packed[k], Xs[k], sxs[k], Ys[k], goq.F16, stream=stream)
 
     for _ in range(warmup):
         step()
@@ -192,19 +197,20 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2):
     ev1.record(stream)
     torch.cuda.synchronize()
     ms = ev0.elapsed_time(ev1) / steps
-    issued = 4.0 * tokens * sum(o * i for _, o, i in shapes)
+    issued = (2.0 if folded else 4.0) * tokens * sum(o * i for _, o, i in shapes)
     # the peak of the matrix instruction the path runs on: fp16 for A16 and for bw = 4 with
     # integer activations (widened to fp16), int8 otherwise
     f16_path = act == goq.A16 or bw == 4
     peak = MFMA_F16_PEAK_TFLOPS if f16_path else MFMA_I8_PEAK_TOPS
     tops = issued / (ms * 1e-3) / 1e12
     return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, {goq.A16: "A16", goq.A8: "A8", goq.A4: "A4"}[act]),
-            "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1), "dense_equiv_TOPS": round(tops / 2, 1),
+            "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1),
+            "dense_equiv_TOPS": round(tops if folded else tops / 2, 1),
             "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if f16_path else "TOP/s",
                          "frac": round(tops / peak, 4), "traffic": None}}
 
 
-def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
+def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
     """A GEMM workload on its own (BASELINE configs 3, 4 and the GEMM half of 5): one launch per
     matrix per step; value = issued TOPS (4 M N K per matrix)."""
     import torch
@@ -222,14 +228,15 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name):
         goq.pack(bw, out, inn, *d, pk)
         torch.cuda.synchronize()
         packed.append(pk)
-    g = bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=max(3, min(args.steps, 20)), warmup=2)
+    g = bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=max(3, min(args.steps, 20)), warmup=2,
+                         folded=folded)
     res = {
         "metric": "PoT GEMV GB/s (% HBM peak) and GEMM TOPS (% MFMA peak), LLaMA-2-7B shapes",
         "value": g["issued_TOPS"], "unit": g["roofline"]["unit"], "n_gpus": 1, "steps": max(3, min(args.steps, 20)),
         "warmup": 2, "ms_per_step": g["ms_per_block"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if (act_name == "A16" or bw == 4) else "i8", "data": "synthetic",
         "config": {"workload": name, "bw": bw, "act": act_name, "group": 128, "tokens": tokens, "matrices": len(shapes),
-                   "issued_ops_per_step": 4.0 * tokens * sum(o * i for _, o, i in shapes),
+                   "issued_ops_per_step": (2.0 if folded else 4.0) * tokens * sum(o * i for _, o, i in shapes),
                    "dense_equiv_TOPS": g["dense_equiv_TOPS"]},
         "roofline": g["roofline"],
     }
@@ -437,7 +444,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--settle", type=int, default=3000,
                     help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3", "c3_gemm_folded"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -461,6 +468,10 @@ def main():
         res = bench_ref(args, goq_inputs.LLAMA2_7B_BLOCK, 3, 512, "REF coefficients of a llama2-7b decoder block, W3, 512 calibration tokens")
     elif args.workload == "c3_gemm_w3":
         res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W3/A16")
+    elif args.workload == "c3_gemm_folded":
+        res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "A16", 2048,
+                              "ablation: llama2-7b block GEMMs, 2048 tokens, W3/A16, bases folded to one fp16 weight (2 M N K)",
+                              folded=True)
     elif args.workload == "c3_gemm_w4":
         res = bench_gemm_only(args, goq_inputs.LLAMA2_7B_BLOCK, 4, "A16", 2048, "llama2-7b block GEMMs, 2048 tokens, W4/A16")
     elif args.workload == "c4_gemm_a8":

@@ -164,6 +164,17 @@ int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t
              const void *packed, const void *X, const float *sx, void *Y, int ytype,
              int32_t *partials);
 
+/* Ablation of the two-basis product (not the method's path; it measures what keeping the PoT
+ * operands native costs on matrix-core hardware).  Same result as goq_gemm with GOQ_A16 up to
+ * rounding, computed differently: the decoded bases are combined in registers to the fp16 weight
+ * c1 b1 + c2 b2 of Eq. 4's slab and ONE fp16 matrix instruction per k-step accumulates into Y in
+ * fp32 -- half the matrix instructions, no per-slab rescale, but every weight is rounded to fp16
+ * (relative 2^-11), so the result is held to 1e-3 normalised backward error
+ * |y - y^| / sum_k |x_k| |W^_k| only, not to the element-wise bound of goq_gemm.  X fp16
+ * [tokens][in], Y [tokens][out] of ytype; arguments and errors as for goq_gemm. */
+int goq_gemm_folded(void *stream, int bw, int64_t tokens, int64_t out, int64_t in,
+                    const void *packed, const void *X, void *Y, int ytype);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,7 @@ GEMV_AUTO, GEMV_STREAM, GEMV_ROWS = 0, 1, 2
 
 EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_ref_workspace_bytes",
            "goq_ref_coefficients", "goq_pack", "goq_unpack",
-           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemm"]
+           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemm", "goq_gemm_folded"]
 
 
 class GoqError(RuntimeError):
@@ -53,6 +53,7 @@ def lib():
         L.goq_gemv_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc)]
         L.goq_gemv_select.argtypes = [i]
         L.goq_gemm.argtypes = [vp, i, i, i64, i64, i64, vp, vp, vp, vp, i, vp]
+        L.goq_gemm_folded.argtypes = [vp, i, i64, i64, i64, vp, vp, vp, i]
         _lib = L
     return _lib
 
@@ -141,3 +142,7 @@ def gemv_batch(bw, act, problems, stream=None):
 def gemm(bw, act, tokens, out, inn, packed, X, sx, Y, ytype, partials=None, stream=None):
     _check(lib().goq_gemm(_stream(stream), bw, act, tokens, out, inn, _ptr(packed), _ptr(X), _ptr(sx),
                           _ptr(Y), ytype, _ptr(partials)))
+
+
+def gemm_folded(bw, tokens, out, inn, packed, X, Y, ytype, stream=None):
+    _check(lib().goq_gemm_folded(_stream(stream), bw, tokens, out, inn, _ptr(packed), _ptr(X), _ptr(Y), ytype))

@@ -172,4 +172,17 @@ int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t
     return goq_launch_gemm((hipStream_t)stream, bw, act, tokens, out, in, packed, X, sx, Y, ytype, partials);
 }
 
+int goq_gemm_folded(void *stream, int bw, int64_t tokens, int64_t out, int64_t in, const void *packed,
+                    const void *X, void *Y, int ytype)
+{
+    int rc = check_shape("goq_gemm_folded", bw, out, in);
+    if (rc) return rc;
+    if (tokens <= 0 || tokens > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "goq_gemm_folded: tokens = %lld out of range", (long long)tokens);
+    if (ytype != GOQ_F16 && ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "goq_gemm_folded: bad output type %d", ytype);
+    if (!packed || !X || !Y) return goq_set_error(GOQ_EINVAL, "goq_gemm_folded: NULL pointer");
+    if (misaligned(packed, 16) || misaligned(X, 16) || misaligned(Y, 16))
+        return goq_set_error(GOQ_EINVAL, "goq_gemm_folded: packed, X and Y must be 16-byte aligned");
+    return goq_launch_gemm_folded((hipStream_t)stream, bw, tokens, out, in, packed, X, Y, ytype);
+}
+
 }  // extern "C"

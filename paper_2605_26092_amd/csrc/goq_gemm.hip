@@ -144,9 +144,15 @@ __device__ __forceinline__ f16x8 widen8(uint32_t lo, uint32_t hi)
 #ifndef GOQ_GEMM_MINWAVES
 #define GOQ_GEMM_MINWAVES 2
 #endif
-template <int BW, int ACT, bool PART>
+// FOLD (fp16 activations only) is the ablation of the method's two-basis product: the decoded
+// operands are combined in registers to the fp16 weight c1 b1 + c2 b2 (two packed fp16 operations
+// per register) and ONE matrix instruction per k-step and tile accumulates straight into Y.  Half
+// the matrix instructions and no rescale, but the operand is no power of two any more: every
+// weight is rounded to fp16 (2^-11 relative), which the two-basis path avoids.
+template <int BW, int ACT, bool PART, bool FOLD = false>
 __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a)
 {
+    static_assert(!FOLD || (ACT == 0 && !PART), "the folded product exists for fp16 activations only");
     constexpr int CH = (BW == 3) ? 4 : 5;
     // ACT: 0 fp16 x; 1 int8 x, int8 MFMA; 2 int8 x widened to fp16; 3 packed int4 x unpacked to
     // int8, int8 MFMA; 4 packed int4 x widened to fp16.  2..4 stage x through registers.
@@ -315,13 +321,16 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                     make_uint4(o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]);
         }
     };
-    // decoded B operands (b1 and b2) of k-step t of a slab (H2, H4)
+    // decoded B operands (b1 and b2) of k-step t of a slab (H2, H4); cf (FOLD): the slab's
+    // coefficients (c1, c2) as fp16, both halves of a register alike
+    f16x8 cf1, cf2;
     auto decode_step = [&](const Weights &w, int t, OpT &B1, OpT &B2) {
         if constexpr (F16) {
             uint32_t l1, h1, l2, h2;
             decode_pair<BW, WACT>(word_of(w, t), w.meta, t, vt, l1, h1, l2, h2);
             B1 = widen8(l1, h1);
             B2 = widen8(l2, h2);
+            if constexpr (FOLD) B1 = cf1 * B1 + cf2 * B2;
         } else {
             uint32_t l1, h1, l2, h2, l3, h3, l4, h4;
             decode_pair<BW, WACT>(word_of(w, 2 * t), w.meta, 2 * t, vt, l1, h1, l2, h2);
@@ -373,7 +382,14 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
+    auto fold_coefficients = [&](const Weights &w) {
+        float c1, c2;
+        coefficients(w, c1, c2);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { cf1[k] = (_Float16)c1; cf2[k] = (_Float16)c2; }
+    };
     OpT B1, B2, A[MS];
+    if constexpr (FOLD) fold_coefficients(wd);
     decode_step(wd, 0, B1, B2);
     read_a(xsb[0], 0, A);
 
@@ -389,8 +405,8 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
             if (more2) stage_x(g + 2);
         }
 
-        float c1, c2;
-        coefficients(wd, c1, c2);
+        float c1 = 0.f, c2 = 0.f;
+        if constexpr (!FOLD) coefficients(wd, c1, c2);
 
         AccT P1[MS], P2[MS];
 #pragma unroll
@@ -415,6 +431,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 }
                 __syncthreads();
+                if constexpr (FOLD) fold_coefficients(wn);
                 decode_step(wn, 0, B1, B2);
                 read_a(xsb[min(g + 1, a.gn - 1) % NBUF], 0, A);
             }
@@ -423,7 +440,9 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
                 AccT z;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) z[v] = 0;
-                if constexpr (F16) {
+                if constexpr (FOLD) {
+                    Yacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B1c, Yacc[i], 0, 0, 0);
+                } else if constexpr (F16) {
                     P1[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B1c, t == 0 ? z : P1[i], 0, 0, 0);
                     P2[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Ac[i], B2c, t == 0 ? z : P2[i], 0, 0, 0);
                 } else {
@@ -436,10 +455,12 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
         //      of a 32 x 32 tile: token 8 (v / 4) + 4 kg + v % 4, output ln.
 #pragma unroll
         for (int i = 0; i < MS; ++i) {
+            if constexpr (!FOLD) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                Yacc[i][v] = fmaf(c1, (float)P1[i][v], Yacc[i][v]);
-                Yacc[i][v] = fmaf(c2, (float)P2[i][v], Yacc[i][v]);
+                for (int v = 0; v < 16; ++v) {
+                    Yacc[i][v] = fmaf(c1, (float)P1[i][v], Yacc[i][v]);
+                    Yacc[i][v] = fmaf(c2, (float)P2[i][v], Yacc[i][v]);
+                }
             }
             if constexpr (PART) {
                 // exact int32 slab partials [tokens][out][in/128][2] (verification output)
@@ -486,7 +507,34 @@ int launch(hipStream_t st, const GemmArgs &a)
     return goq_check_launch("goq_gemm");
 }
 
+template <int BW>
+int launch_folded(hipStream_t st, const GemmArgs &a)
+{
+    const int mtiles = (a.tokens + TM - 1) / TM;
+    const int ntiles = (a.out + TN - 1) / TN;
+    hipLaunchKernelGGL((gemm_kernel<BW, 0, false, true>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
+    return goq_check_launch("goq_gemm_folded");
+}
+
 }  // namespace
+
+int goq_launch_gemm_folded(hipStream_t st, int bw, int64_t tokens, int64_t out, int64_t in, const void *packed,
+                           const void *X, void *Y, int ytype)
+{
+    GemmArgs a;
+    a.packed = (const uint32_t *)packed;
+    a.X = X;
+    a.sx = nullptr;
+    a.Y = Y;
+    a.partials = nullptr;
+    a.tokens = (int)tokens;
+    a.out = (int)out;
+    a.in = (int)in;
+    a.gn = (int)(in / GOQ_N);
+    a.rbn = (int)goq_row_blocks(out);
+    a.ytype = ytype;
+    return bw == 3 ? launch_folded<3>(st, a) : launch_folded<4>(st, a);
+}
 
 int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out, int64_t in,
                     const void *packed, const void *X, const float *sx, void *Y, int ytype,

@@ -163,3 +163,30 @@ def test_gemm_config4_sampled(oracle):
     assert np.array_equal(parts[idx].cpu().numpy(), rp)
     y = Y[idx].cpu().numpy().astype(np.float64)
     assert np.max(np.abs(y - ref)) <= 1e-5 * np.max(np.abs(ref))
+
+
+@pytest.mark.parametrize("bw", [3, 4])
+@pytest.mark.parametrize("shape", [(5, 64, 128), (17, 130, 384), (200, 384, 1024), (257, 1100, 512)])
+def test_gemm_folded_ablation(oracle, bw, shape):
+    """goq_gemm_folded rounds every weight c1 b1 + c2 b2 to fp16 (relative 2^-11 = 4.9e-4) before
+    the product: normalised backward error <= 1e-3 against the oracle, and it agrees with goq_gemm
+    to the same bound."""
+    import paper_2605_26092_amd as goq
+    torch = gu.torch_cuda()
+    tokens, out, inn = shape
+    print("gemm folded bw=%d tokens=%d out=%d in=%d" % (bw, tokens, out, inn), flush=True)
+    q = _quantize(oracle, bw, out, inn, 46)
+    X = goq_inputs.activations_a16(tokens, inn, config_id=46, tensor_id=100 + tokens, outlier_frac=0.01)
+    ref = oracle.gemm_a16(q, X, threads=8)
+    what_abs = np.abs(oracle.dequant(q, want=("what",))["what"])
+    packed = gu.pack_layer(goq, q)
+    Xd = gu.to_dev(X)
+    Y = torch.full((tokens, out), float("nan"), dtype=torch.float32, device="cuda")
+    goq.gemm_folded(bw, tokens, out, inn, packed, Xd, Y, goq.F32)
+    torch.cuda.synchronize()
+    y = Y.cpu().numpy().astype(np.float64)
+    _, e2 = gu.a16_errors(y, ref, X, what_abs)
+    assert e2 <= TOL, e2
+    Y2, _ = _gemm(goq, q, X, goq.A16, goq.F32)
+    _, d2 = gu.a16_errors(y, Y2.cpu().numpy().astype(np.float64), X, what_abs)
+    assert d2 <= TOL, d2
