@@ -444,7 +444,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--settle", type=int, default=3000,
                     help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3", "c3_gemm_folded"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3", "c3_gemm_folded", "c2_gemv_w4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -457,6 +457,8 @@ def main():
         sys.exit(2)
     if args.workload == "c2_gemv":
         res = bench_gemv(args, goq_inputs.LLAMA2_7B_BLOCK, 3, "llama2-7b decoder block, 7 GEMVs, W3/A16, batch 1")
+    elif args.workload == "c2_gemv_w4":
+        res = bench_gemv(args, goq_inputs.LLAMA2_7B_BLOCK, 4, "llama2-7b decoder block, 7 GEMVs, W4/A16, batch 1")
     elif args.workload == "c1_gemv":
         res = bench_gemv(args, [("l", 4096, 4096)], 3, "single 4096x4096 layer, W3/A16, batch 1")
     elif args.workload == "c5_gemv":
