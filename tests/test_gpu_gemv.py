@@ -53,10 +53,11 @@ def _run_gemv(goq, q, x_np, act, ytype, sx_np=None):
 @pytest.mark.parametrize("bw", [3, 4])
 @pytest.mark.parametrize("ytype_name", ["F32", "F16"])
 @pytest.mark.parametrize("shape", [(1, 128), (64, 128), (3, 256), (17, 384), (200, 512), (1100, 1024), (600, 4096),
-                                   (150, 6400), (8300, 256)])
+                                   (150, 6400), (8300, 256), (40, 4224), (33, 8192)])
 def test_gemv_a16_small(oracle, bw, ytype_name, shape):
     """(8300, 256) has more 16-row tiles than the automatic choice gives the row-owner kernel;
-    6400 = 50 macro-blocks spans two of that kernel's staging windows."""
+    6400 = 50 macro-blocks spans two of that kernel's staging windows, 4224 = 33 leaves a single
+    macro-block for the second window, 8192 = 64 fills two windows exactly."""
     import paper_2605_26092_amd as goq
     out, inn = shape
     q = _quantize(oracle, bw, out, inn, 31)
@@ -74,7 +75,7 @@ def test_gemv_a16_small(oracle, bw, ytype_name, shape):
 
 
 @pytest.mark.parametrize("bw", [3, 4])
-@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (17, 384), (200, 768), (1100, 1024), (150, 6400)])
+@pytest.mark.parametrize("shape", [(1, 128), (64, 128), (17, 384), (200, 768), (1100, 1024), (150, 6400), (40, 4224)])
 def test_gemv_a8(oracle, bw, shape):
     import paper_2605_26092_amd as goq
     out, inn = shape
