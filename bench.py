@@ -203,11 +203,20 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, 
     f16_path = act == goq.A16 or bw == 4
     peak = MFMA_F16_PEAK_TFLOPS if f16_path else MFMA_I8_PEAK_TOPS
     tops = issued / (ms * 1e-3) / 1e12
+    # HBM traffic per launch (mean over the block's matrices) from the committed counter runs, if
+    # they cover this workload: the 7B block at 2048 tokens, W3/A16
+    traffic = None
+    if bw == 3 and act == goq.A16 and tokens == 2048 and not folded and len(shapes) == 7 and shapes[0][1] == 4096:
+        try:
+            with open(os.path.join(ROOT, "profiles", "traffic.json.txt")) as fh:
+                traffic = json.load(fh)["gemm_kernel<3,0,false>"]["hbm_bytes_per_launch"]
+        except (OSError, KeyError, ValueError):
+            pass
     return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, {goq.A16: "A16", goq.A8: "A8", goq.A4: "A4"}[act]),
             "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1),
             "dense_equiv_TOPS": round(tops if folded else tops / 2, 1),
             "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if f16_path else "TOP/s",
-                         "frac": round(tops / peak, 4), "traffic": None}}
+                         "frac": round(tops / peak, 4), "traffic": traffic}}
 
 
 def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
