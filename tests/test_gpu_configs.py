@@ -1,7 +1,7 @@
 """BASELINE configs 2 and 5 at full size, in the launch configuration bench.py times.
 
-Config 2: the seven LLaMA-2-7B block GEMVs as ONE goq_gemv_batch launch, every output checked
-against the oracle.  Config 5: LLaMA-2-70B shapes (k: 1024 x 8192, down: 8192 x 28672) as GEMV
+Config 2: the seven LLaMA-2-7B block GEMVs as ONE goq_gemv_batch launch (W3 as in the config, and
+W4), every output checked against the oracle.  Config 5: LLaMA-2-70B shapes (k: 1024 x 8192, down: 8192 x 28672) as GEMV
 (all outputs) and as a 512-token GEMM (a seeded sample of token rows, all outputs)."""
 import numpy as np
 import pytest
@@ -18,13 +18,14 @@ def _quantize(oracle, bw, out, inn, cid, tid):
     return oracle.quantize_geo(bw, W, threads=16)
 
 
-def test_config2_block_gemv_batch(oracle):
+@pytest.mark.parametrize("bw", [3, 4])
+def test_config2_block_gemv_batch(oracle, bw):
     import paper_2605_26092_amd as goq
     torch = gu.torch_cuda()
     probs, refs, ys, keep = [], [], [], []
     for idx, (name, out, inn) in enumerate(goq_inputs.LLAMA2_7B_BLOCK):
-        print("config2 %s %dx%d" % (name, out, inn), flush=True)
-        q = _quantize(oracle, 3, out, inn, 2, idx)
+        print("config2 bw=%d %s %dx%d" % (bw, name, out, inn), flush=True)
+        q = _quantize(oracle, bw, out, inn, 2, idx)
         x = goq_inputs.activations_a16(1, inn, config_id=2, tensor_id=100 + idx, outlier_frac=0.01)
         refs.append(oracle.gemm_a16(q, x, threads=16)[0])
         packed = gu.pack_layer(goq, q)
@@ -35,7 +36,7 @@ def test_config2_block_gemv_batch(oracle):
         probs.append((out, inn, packed, xd, None, y, goq.F32))
         del q
     for rep in range(2):                       # a second launch must not accumulate onto the first
-        goq.gemv_batch(3, goq.A16, probs)
+        goq.gemv_batch(bw, goq.A16, probs)
     torch.cuda.synchronize()
     for (name, _, _), y, ref in zip(goq_inputs.LLAMA2_7B_BLOCK, ys, refs):
         e1, _ = gu.a16_errors(y.cpu().numpy(), ref, None)
