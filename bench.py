@@ -156,7 +156,7 @@ def gemv_kernel_name(bw, shapes):
 
 
 def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, folded=False):
-    """The same block as many-token GEMMs (one launch per matrix): issued ops = 4 M N K (two PoT
+    """The same block as many-token GEMMs (one goq_gemm_batch launch): issued ops = 4 M N K (two PoT
     bases), dense-equivalent = 2 M N K.  Reported next to the headline, not instead of it.
     folded: the ablation goq_gemm_folded (one contraction with the fp16 weight c1 b1 + c2 b2):
     issued = dense-equivalent = 2 M N K."""
@@ -179,12 +179,16 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, 
         Ys.append(torch.zeros((tokens, out), dtype=torch.float16, device=dev))
     stream = torch.cuda.current_stream()
 
+    from paper_2605_26092_amd import binding
+    descs = binding.make_gemm_descs([(tokens, out, inn, packed[k], Xs[k], sxs[k], Ys[k], goq.F16)
+                                     for k, (_, out, inn) in enumerate(shapes)])
+
     def step():
-        for k, (_, out, inn) in enumerate(shapes):
-            if folded:
+        if folded:                   # the ablation has no batched entry point: one launch per matrix
+            for k, (_, out, inn) in enumerate(shapes):
                 goq.gemm_folded(bw, tokens, out, inn, packed[k], Xs[k], Ys[k], goq.F16, stream=stream)
-            else:
-                goq.gemm(bw, act, tokens, out, inn, packed[k], Xs[k], sxs[k], Ys[k], goq.F16, stream=stream)
+        else:                        # the block's matrices as one grid (goq_gemm_batch)
+            goq.gemm_batch(bw, act, descs, stream=stream)
 
     for _ in range(warmup):
         step()
@@ -220,8 +224,8 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, 
 
 
 def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
-    """A GEMM workload on its own (BASELINE configs 3, 4 and the GEMM half of 5): one launch per
-    matrix per step; value = issued TOPS (4 M N K per matrix)."""
+    """A GEMM workload on its own (BASELINE configs 3, 4 and the GEMM half of 5): the block's
+    matrices in one goq_gemm_batch launch per step; value = issued TOPS (4 M N K per matrix)."""
     import torch
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")

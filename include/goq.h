@@ -164,6 +164,22 @@ int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t
              const void *packed, const void *X, const float *sx, void *Y, int ytype,
              int32_t *partials);
 
+/* Several independent many-token layers in ONE launch (e.g. q, k, v or gate, up of a decoder block,
+ * which share X): the tiles of all problems form one grid, so a small matrix does not leave the
+ * chip half empty and there is one tail instead of n.  descs is a HOST array of n <= GOQ_MAX_BATCH
+ * descriptors with the arguments of goq_gemm; all share bw and act.  Results are those of n
+ * goq_gemm calls, bit for bit. */
+typedef struct goq_gemm_desc {
+    int64_t tokens, out, in;
+    const void *packed;
+    const void *X;
+    const float *sx;
+    void *Y;
+    int ytype;
+    int32_t *partials;
+} goq_gemm_desc;
+int goq_gemm_batch(void *stream, int bw, int act, int n, const goq_gemm_desc *descs);
+
 /* Ablation of the two-basis product (not the method's path; it measures what keeping the PoT
  * operands native costs on matrix-core hardware).  Same result as goq_gemm with GOQ_A16 up to
  * rounding, computed differently: the decoded bases are combined in registers to the fp16 weight

@@ -18,13 +18,19 @@ GEMV_AUTO, GEMV_STREAM, GEMV_ROWS = 0, 1, 2
 
 EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_ref_workspace_bytes",
            "goq_ref_coefficients", "goq_pack", "goq_unpack",
-           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemm", "goq_gemm_folded"]
+           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemm", "goq_gemm_batch", "goq_gemm_folded"]
 
 
 class GoqError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__("goq error %d: %s" % (code, msg))
         self.code = code
+
+
+class _GemmDesc(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int64), ("out", ctypes.c_int64), ("in_", ctypes.c_int64),
+                ("packed", ctypes.c_void_p), ("X", ctypes.c_void_p), ("sx", ctypes.c_void_p),
+                ("Y", ctypes.c_void_p), ("ytype", ctypes.c_int), ("partials", ctypes.c_void_p)]
 
 
 class _Desc(ctypes.Structure):
@@ -53,6 +59,7 @@ def lib():
         L.goq_gemv_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc)]
         L.goq_gemv_select.argtypes = [i]
         L.goq_gemm.argtypes = [vp, i, i, i64, i64, i64, vp, vp, vp, vp, i, vp]
+        L.goq_gemm_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_GemmDesc)]
         L.goq_gemm_folded.argtypes = [vp, i, i64, i64, i64, vp, vp, vp, i]
         _lib = L
     return _lib
@@ -146,3 +153,18 @@ def gemm(bw, act, tokens, out, inn, packed, X, sx, Y, ytype, partials=None, stre
 
 def gemm_folded(bw, tokens, out, inn, packed, X, Y, ytype, stream=None):
     _check(lib().goq_gemm_folded(_stream(stream), bw, tokens, out, inn, _ptr(packed), _ptr(X), _ptr(Y), ytype))
+
+
+def make_gemm_descs(problems):
+    """problems: list of (tokens, out, in, packed, X, sx, Y, ytype[, partials]) -> ctypes array (host memory)."""
+    arr = (_GemmDesc * len(problems))()
+    for d, p in zip(arr, problems):
+        tokens, out, inn, packed, X, sx, Y, ytype = p[:8]
+        d.tokens, d.out, d.in_, d.packed, d.X, d.sx, d.Y, d.ytype = tokens, out, inn, _ptr(packed), _ptr(X), _ptr(sx), _ptr(Y), ytype
+        d.partials = _ptr(p[8]) if len(p) > 8 else None
+    return arr
+
+
+def gemm_batch(bw, act, problems, stream=None):
+    arr = problems if isinstance(problems, ctypes.Array) else make_gemm_descs(problems)
+    _check(lib().goq_gemm_batch(_stream(stream), bw, act, len(arr), arr))

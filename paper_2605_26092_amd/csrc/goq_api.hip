@@ -155,21 +155,43 @@ int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *de
     return goq_launch_gemv((hipStream_t)stream, bw, act, n, descs);
 }
 
+static int check_gemm_desc(const char *fn, int bw, int act, const goq_gemm_desc &d)
+{
+    int rc = check_shape(fn, bw, d.out, d.in);
+    if (rc) return rc;
+    if (d.tokens <= 0 || d.tokens > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "%s: tokens = %lld out of range", fn, (long long)d.tokens);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
+    if (d.ytype != GOQ_F16 && d.ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "%s: bad output type %d", fn, d.ytype);
+    if (!d.packed || !d.X || !d.Y) return goq_set_error(GOQ_EINVAL, "%s: NULL pointer", fn);
+    if (act != GOQ_A16 && !d.sx) return goq_set_error(GOQ_EINVAL, "%s: integer activations need sx", fn);
+    if (act == GOQ_A16 && d.sx) return goq_set_error(GOQ_EINVAL, "%s: sx must be NULL for fp16 activations", fn);
+    if (act == GOQ_A16 && d.partials) return goq_set_error(GOQ_EINVAL, "%s: partials is only defined for int8 activations", fn);
+    if (misaligned(d.packed, 16) || misaligned(d.X, 16) || misaligned(d.Y, 16))
+        return goq_set_error(GOQ_EINVAL, "%s: packed, X and Y must be 16-byte aligned", fn);
+    return GOQ_OK;
+}
+
 int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t in, const void *packed,
              const void *X, const float *sx, void *Y, int ytype, int32_t *partials)
 {
-    int rc = check_shape("goq_gemm", bw, out, in);
+    goq_gemm_desc d;
+    d.tokens = tokens; d.out = out; d.in = in; d.packed = packed; d.X = X; d.sx = sx; d.Y = Y;
+    d.ytype = ytype; d.partials = partials;
+    int rc = check_gemm_desc("goq_gemm", bw, act, d);
     if (rc) return rc;
-    if (tokens <= 0 || tokens > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "goq_gemm: tokens = %lld out of range", (long long)tokens);
-    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad activation type %d", act);
-    if (ytype != GOQ_F16 && ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "goq_gemm: bad output type %d", ytype);
-    if (!packed || !X || !Y) return goq_set_error(GOQ_EINVAL, "goq_gemm: NULL pointer");
-    if (act != GOQ_A16 && !sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: integer activations need sx");
-    if (act == GOQ_A16 && sx) return goq_set_error(GOQ_EINVAL, "goq_gemm: sx must be NULL for fp16 activations");
-    if (act == GOQ_A16 && partials) return goq_set_error(GOQ_EINVAL, "goq_gemm: partials is only defined for int8 activations");
-    if (misaligned(packed, 16) || misaligned(X, 16) || misaligned(Y, 16))
-        return goq_set_error(GOQ_EINVAL, "goq_gemm: packed, X and Y must be 16-byte aligned");
-    return goq_launch_gemm((hipStream_t)stream, bw, act, tokens, out, in, packed, X, sx, Y, ytype, partials);
+    return goq_launch_gemm((hipStream_t)stream, bw, act, 1, &d);
+}
+
+int goq_gemm_batch(void *stream, int bw, int act, int n, const goq_gemm_desc *descs)
+{
+    if (!descs) return goq_set_error(GOQ_EINVAL, "goq_gemm_batch: descs is NULL");
+    if (n < 1 || n > GOQ_MAX_BATCH)
+        return goq_set_error(GOQ_ESHAPE, "goq_gemm_batch: n = %d must be in 1..%d", n, GOQ_MAX_BATCH);
+    for (int i = 0; i < n; ++i) {
+        int rc = check_gemm_desc("goq_gemm_batch", bw, act, descs[i]);
+        if (rc) return rc;
+    }
+    return goq_launch_gemm((hipStream_t)stream, bw, act, n, descs);
 }
 
 int goq_gemm_folded(void *stream, int bw, int64_t tokens, int64_t out, int64_t in, const void *packed,

@@ -66,6 +66,13 @@ struct GemmArgs {
     int tokens, out, in, gn, rbn, ytype;
 };
 
+// The problems of one launch: workgroups first[i] .. first[i + 1] - 1 own the tiles of problem i
+// (unused problems start at INT_MAX).
+struct GemmBatch {
+    int first[GOQ_MAX_BATCH];
+    GemmArgs p[GOQ_MAX_BATCH];
+};
+
 // Exchange table entry of variant v = pattern | signs << 2 (Theorem 1):
 //   x, y : v_perm selectors, byte i of b2 = byte (i xor s) of b1
 //   z, w : per-byte masks of the elements whose sign flips (0x80 for fp16 high bytes, 0xFF for
@@ -150,8 +157,14 @@ __device__ __forceinline__ f16x8 widen8(uint32_t lo, uint32_t hi)
 // the matrix instructions and no rescale, but the operand is no power of two any more: every
 // weight is rounded to fp16 (2^-11 relative), which the two-basis path avoids.
 template <int BW, int ACT, bool PART, bool FOLD = false>
-__global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a)
+__global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch batch)
 {
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < GOQ_MAX_BATCH; ++i) pi += ((int)blockIdx.x >= batch.first[i]) ? 1 : 0;
+    pi = __builtin_amdgcn_readfirstlane(pi);
+    const GemmArgs &a = batch.p[pi];
+    const int tile = (int)blockIdx.x - batch.first[pi];
     static_assert(!FOLD || (ACT == 0 && !PART), "the folded product exists for fp16 activations only");
     constexpr int CH = (BW == 3) ? 4 : 5;
     // ACT: 0 fp16 x; 1 int8 x, int8 MFMA; 2 int8 x widened to fp16; 3 packed int4 x unpacked to
@@ -177,8 +190,8 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
     const int kg = lane >> 5;     // k-group
 
     const int mtiles = (a.tokens + TM - 1) / TM;
-    const int mt = blockIdx.x % mtiles;
-    const int nt = blockIdx.x / mtiles;
+    const int mt = tile % mtiles;
+    const int nt = tile / mtiles;
     const int m0 = mt * TM;
     const int n0 = nt * TN + wave * WN;
 
@@ -468,7 +481,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + 32 * i + 8 * (v / 4) + 4 * kg + (v % 4);
-                    if (m < a.tokens && n < a.out)
+                    if (m < a.tokens && n < a.out && a.partials)
                         *reinterpret_cast<int2 *>(a.partials + (((int64_t)m * a.out + n) * a.gn + g) * 2) =
                             F16 ? make_int2((int)((float)P1[i][v] * (float)(1 << ((1 << (BW - 1)) - 1))),
                                             (int)((float)P2[i][v] * (float)(1 << ((1 << (BW - 1)) - 1))))
@@ -495,25 +508,57 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmArgs a
         }
 }
 
-template <int BW, int ACT>
-int launch(hipStream_t st, const GemmArgs &a)
+// tiles of the problems, in launch order; returns the grid size (0: too large)
+int64_t lay_out(GemmBatch &b, int n)
 {
-    const int mtiles = (a.tokens + TM - 1) / TM;
-    const int ntiles = (a.out + TN - 1) / TN;
-    if (ACT != 0 && a.partials)
-        hipLaunchKernelGGL((gemm_kernel<BW, ACT, (ACT != 0)>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
+    int64_t tiles = 0;
+    for (int i = 0; i < GOQ_MAX_BATCH; ++i) {
+        if (i >= n) { b.first[i] = 0x7fffffff; b.p[i] = b.p[0]; continue; }
+        b.first[i] = (int)tiles;
+        tiles += (int64_t)((b.p[i].tokens + TM - 1) / TM) * ((b.p[i].out + TN - 1) / TN);
+        if (tiles > 0x3fffffff) return 0;
+    }
+    return tiles;
+}
+
+template <int BW, int ACT>
+int launch(hipStream_t st, GemmBatch &b, int n)
+{
+    const int64_t grid = lay_out(b, n);
+    if (!grid) return goq_set_error(GOQ_ESHAPE, "goq_gemm: too much work for one launch");
+    bool part = false;
+    for (int i = 0; i < n; ++i) part = part || b.p[i].partials;
+    if (ACT != 0 && part)
+        hipLaunchKernelGGL((gemm_kernel<BW, ACT, (ACT != 0)>), dim3((unsigned)grid), dim3(256), 0, st, b);
     else
-        hipLaunchKernelGGL((gemm_kernel<BW, ACT, false>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
+        hipLaunchKernelGGL((gemm_kernel<BW, ACT, false>), dim3((unsigned)grid), dim3(256), 0, st, b);
     return goq_check_launch("goq_gemm");
 }
 
 template <int BW>
-int launch_folded(hipStream_t st, const GemmArgs &a)
+int launch_folded(hipStream_t st, GemmBatch &b, int n)
 {
-    const int mtiles = (a.tokens + TM - 1) / TM;
-    const int ntiles = (a.out + TN - 1) / TN;
-    hipLaunchKernelGGL((gemm_kernel<BW, 0, false, true>), dim3(mtiles * ntiles), dim3(256), 0, st, a);
+    const int64_t grid = lay_out(b, n);
+    if (!grid) return goq_set_error(GOQ_ESHAPE, "goq_gemm_folded: too much work for one launch");
+    hipLaunchKernelGGL((gemm_kernel<BW, 0, false, true>), dim3((unsigned)grid), dim3(256), 0, st, b);
     return goq_check_launch("goq_gemm_folded");
+}
+
+GemmArgs make_args(const goq_gemm_desc &d)
+{
+    GemmArgs a;
+    a.packed = (const uint32_t *)d.packed;
+    a.X = d.X;
+    a.sx = d.sx;
+    a.Y = d.Y;
+    a.partials = d.partials;
+    a.tokens = (int)d.tokens;
+    a.out = (int)d.out;
+    a.in = (int)d.in;
+    a.gn = (int)(d.in / GOQ_N);
+    a.rbn = (int)goq_row_blocks(d.out);
+    a.ytype = d.ytype;
+    return a;
 }
 
 }  // namespace
@@ -521,41 +566,22 @@ int launch_folded(hipStream_t st, const GemmArgs &a)
 int goq_launch_gemm_folded(hipStream_t st, int bw, int64_t tokens, int64_t out, int64_t in, const void *packed,
                            const void *X, void *Y, int ytype)
 {
-    GemmArgs a;
-    a.packed = (const uint32_t *)packed;
-    a.X = X;
-    a.sx = nullptr;
-    a.Y = Y;
-    a.partials = nullptr;
-    a.tokens = (int)tokens;
-    a.out = (int)out;
-    a.in = (int)in;
-    a.gn = (int)(in / GOQ_N);
-    a.rbn = (int)goq_row_blocks(out);
-    a.ytype = ytype;
-    return bw == 3 ? launch_folded<3>(st, a) : launch_folded<4>(st, a);
+    goq_gemm_desc d;
+    d.tokens = tokens; d.out = out; d.in = in; d.packed = packed; d.X = X; d.sx = nullptr; d.Y = Y;
+    d.ytype = ytype; d.partials = nullptr;
+    GemmBatch b;
+    b.p[0] = make_args(d);
+    return bw == 3 ? launch_folded<3>(st, b, 1) : launch_folded<4>(st, b, 1);
 }
 
-int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out, int64_t in,
-                    const void *packed, const void *X, const float *sx, void *Y, int ytype,
-                    int32_t *partials)
+int goq_launch_gemm(hipStream_t st, int bw, int act, int n, const goq_gemm_desc *descs)
 {
-    GemmArgs a;
-    a.packed = (const uint32_t *)packed;
-    a.X = X;
-    a.sx = sx;
-    a.Y = Y;
-    a.partials = partials;
-    a.tokens = (int)tokens;
-    a.out = (int)out;
-    a.in = (int)in;
-    a.gn = (int)(in / GOQ_N);
-    a.rbn = (int)goq_row_blocks(out);
-    a.ytype = ytype;
-    if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a);
-    if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, a);
-    if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, a);
-    if (bw == 4 && act == GOQ_A8) return launch<4, 2>(st, a);
-    if (bw == 3 && act == GOQ_A4) return launch<3, 3>(st, a);
-    return launch<4, 4>(st, a);
+    GemmBatch b;
+    for (int i = 0; i < n; ++i) b.p[i] = make_args(descs[i]);
+    if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, b, n);
+    if (bw == 3 && act == GOQ_A8) return launch<3, 1>(st, b, n);
+    if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, b, n);
+    if (bw == 4 && act == GOQ_A8) return launch<4, 2>(st, b, n);
+    if (bw == 3 && act == GOQ_A4) return launch<3, 3>(st, b, n);
+    return launch<4, 4>(st, b, n);
 }

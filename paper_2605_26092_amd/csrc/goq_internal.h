@@ -22,6 +22,4 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
 void goq_gemv_set_kernel(int kernel);
 int goq_launch_gemm_folded(hipStream_t st, int bw, int64_t tokens, int64_t out, int64_t in, const void *packed,
                            const void *X, void *Y, int ytype);
-int goq_launch_gemm(hipStream_t st, int bw, int act, int64_t tokens, int64_t out, int64_t in,
-                    const void *packed, const void *X, const float *sx, void *Y, int ytype,
-                    int32_t *partials);
+int goq_launch_gemm(hipStream_t st, int bw, int act, int n, const goq_gemm_desc *descs);

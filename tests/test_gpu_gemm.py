@@ -190,3 +190,38 @@ def test_gemm_folded_ablation(oracle, bw, shape):
     Y2, _ = _gemm(goq, q, X, goq.A16, goq.F32)
     _, d2 = gu.a16_errors(y, Y2.cpu().numpy().astype(np.float64), X, what_abs)
     assert d2 <= TOL, d2
+
+
+@pytest.mark.parametrize("bw,act_name", [(3, "A16"), (4, "A16"), (3, "A8"), (4, "A8")])
+def test_gemm_batch_equals_single_calls(oracle, bw, act_name):
+    """goq_gemm_batch: the tiles of several layers in one grid; bit for bit the results of the
+    single calls (which are checked against the oracle above), partials included where asked."""
+    import paper_2605_26092_amd as goq
+    torch = gu.torch_cuda()
+    act = getattr(goq, act_name)
+    shapes = [(70, 200, 256), (130, 64, 512), (33, 1100, 128)]
+    probs, singles, keep = [], [], []
+    for i, (tokens, out, inn) in enumerate(shapes):
+        q = goq_inputs.canonical_random(bw, out, inn, config_id=47, tensor_id=i)
+        packed = gu.pack_layer(goq, q)
+        if act == goq.A16:
+            X = gu.to_dev(goq_inputs.activations_a16(tokens, inn, config_id=47, tensor_id=10 + i))
+            sx = None
+        else:
+            Xq, sxn = goq_inputs.activations_a8(tokens, inn, config_id=47, tensor_id=10 + i)
+            X, sx = gu.to_dev(Xq), gu.to_dev(sxn)
+        want_parts = act != goq.A16 and i != 1                 # a mix of problems with and without
+        Y1 = torch.full((tokens, out), float("nan"), dtype=torch.float32, device="cuda")
+        P1 = torch.full((tokens, out, inn // 128, 2), -7, dtype=torch.int32, device="cuda") if want_parts else None
+        goq.gemm(bw, act, tokens, out, inn, packed, X, sx, Y1, goq.F32, partials=P1)
+        Yb = torch.full((tokens, out), float("nan"), dtype=torch.float32, device="cuda")
+        Pb = torch.full((tokens, out, inn // 128, 2), -7, dtype=torch.int32, device="cuda") if want_parts else None
+        probs.append((tokens, out, inn, packed, X, sx, Yb, goq.F32, Pb))
+        singles.append((Y1, P1, Yb, Pb))
+        keep += [packed, X, sx]
+    goq.gemm_batch(bw, act, probs)
+    torch.cuda.synchronize()
+    for Y1, P1, Yb, Pb in singles:
+        assert torch.equal(Y1, Yb)
+        if P1 is not None:
+            assert torch.equal(P1, Pb)
