@@ -508,9 +508,16 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
         }
 }
 
-// tiles of the problems, in launch order; returns the grid size (0: too large)
+// tiles of the problems, in launch order; returns the grid size (0: too large).  The problems with
+// the deepest rows go first: their tiles take longest, and the launch should end with short ones.
 int64_t lay_out(GemmBatch &b, int n)
 {
+    for (int i = 1; i < n; ++i)
+        for (int j = i; j > 0 && b.p[j].gn > b.p[j - 1].gn; --j) {
+            const GemmArgs t = b.p[j];
+            b.p[j] = b.p[j - 1];
+            b.p[j - 1] = t;
+        }
     int64_t tiles = 0;
     for (int i = 0; i < GOQ_MAX_BATCH; ++i) {
         if (i >= n) { b.first[i] = 0x7fffffff; b.p[i] = b.p[0]; continue; }
