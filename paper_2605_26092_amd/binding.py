@@ -146,6 +146,19 @@ def gemv_batch(bw, act, problems, stream=None):
     _check(lib().goq_gemv_batch(_stream(stream), bw, act, len(arr), arr))
 
 
+def bind_gemv_batch(bw, act, descs, stream=None):
+    """A zero-argument callable that launches goq_gemv_batch on pre-marshalled arguments (descs from
+    make_descs): for callers that launch the same problems many times and want no per-call
+    marshalling."""
+    fn, s, n = lib().goq_gemv_batch, _stream(stream), len(descs)
+
+    def call():
+        rc = fn(s, bw, act, n, descs)
+        if rc:
+            _check(rc)
+    return call
+
+
 def gemm(bw, act, tokens, out, inn, packed, X, sx, Y, ytype, partials=None, stream=None):
     _check(lib().goq_gemm(_stream(stream), bw, act, tokens, out, inn, _ptr(packed), _ptr(X), _ptr(sx),
                           _ptr(Y), ytype, _ptr(partials)))
