@@ -32,6 +32,8 @@
 // Pipeline: activations of slab g + 2 are requested (global_load_lds, straight into one of three
 // LDS buffers) and the weights of slab g + 1 (registers) at the start of slab g; inside a slab
 // every k-step's MFMAs run on operands prepared during the previous k-step; one barrier per slab.
+// One launch covers up to GOQ_MAX_BATCH layers (goq_gemm_batch): their tiles form one grid, the
+// layers with the deepest rows first, so that a block of matrices has one tail, not one per matrix.
 // Coefficient rescale (H5) once per slab: Y += c1[n,g] * P1 + c2[n,g] * P2 in fp32, after the
 // slab's MFMAs; a lane needs one (c1, c2) pair because every accumulator register of a lane
 // belongs to the same output channel.

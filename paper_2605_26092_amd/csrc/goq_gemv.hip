@@ -29,6 +29,9 @@
 // same number of bytes whatever the matrix shapes are.  The coefficient rescale (H5) is two FMAs
 // per row and slab, after the slab's dot products.
 //
+// (Launches of a few hundred 16-row tiles at most -- single layers -- take the second kernel of this
+// file instead, gemv_rows_kernel: one workgroup per 16 rows over the whole depth, no combine.)
+//
 // Where a piece boundary falls inside a row group, each wavefront publishes the partial sums of
 // its 64 rows to a per-library scratch area and the LAST wavefront to arrive (an atomic counter
 // per boundary and row block) adds the parts in workgroup order and stores y: no zero-fill
