@@ -204,38 +204,52 @@ __device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, 
             v[d] = __builtin_bit_cast(uint32_t, hv);
         }
     }
-    // biased exponent (subnormals -> 1) and 11-bit significand of the 8 elements
-    int ex[8];
-    uint32_t mant[8];
+    // largest biased exponent of the run (subnormals count as 1), then of the scale block
     int emax = 1;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const uint32_t hb = (v[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
-        const int e = (hb >> 10) & 31;
-        ex[k] = e ? e : 1;
-        mant[k] = (hb & 1023u) | (e ? 1024u : 0u);
-        emax = max(emax, ex[k]);
-    }
+    for (int d = 0; d < 4; ++d)
+        emax = max(emax, max((int)((v[d] >> 10) & 31u), (int)((v[d] >> 26) & 31u)));
     emax = max(emax, __shfl_xor(emax, 1));              // runs r, r^1, r^4, r^5 form one scale block
     emax = max(emax, __shfl_xor(emax, 4));
-    uint32_t fx[8];                                  // 24-bit fixed point, truncated
+    // 24-bit fixed point below 2^(emax - 14), truncated: |x| 2^(38 - emax) is an integer part of at
+    // most 24 bits, exact in fp32, and the conversion to integer truncates
+    uint32_t fx[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) fx[k] = (mant[k] << 13) >> min(emax - ex[k], 31);
+    for (int k = 0; k < 8; ++k) {
+        const unsigned short hb = (unsigned short)((v[k >> 1] >> (16 * (k & 1))) & 0x7FFFu);
+        fx[k] = (uint32_t)ldexpf((float)__builtin_bit_cast(_Float16, hb), 38 - emax);
+    }
     // sign bytes of elements 0..3 and 4..7
     const uint32_t slo = goq_perm(v[1], v[0], 0x07050301u) & 0x80808080u;
     const uint32_t shi = goq_perm(v[3], v[2], 0x07050301u) & 0x80808080u;
     unsigned char *dst = xt + (r >> 2) * 256 + (r & 3) * 8;
+    // Digit i of an element is bits 23 - 3 i .. 21 - 3 i of its fixed-point value.  The three bytes
+    // of the values are first gathered across four elements (one element per byte), so that a digit
+    // of four elements is a shift and a mask of one register.
+    uint32_t dg[2][8];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        uint32_t pl[3];
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            const uint32_t sel = 0x0c0c0400u + (uint32_t)b * 0x0101u;              // byte b of both sources
+            pl[b] = goq_perm(goq_perm(fx[4 * hf + 3], fx[4 * hf + 2], sel), goq_perm(fx[4 * hf + 1], fx[4 * hf], sel), 0x05040100u);
+        }
+        const uint32_t M = 0x07070707u;
+        dg[hf][0] = (pl[2] >> 5) & M;
+        dg[hf][1] = (pl[2] >> 2) & M;
+        dg[hf][2] = ((pl[2] << 1) & 0x06060606u) | ((pl[1] >> 7) & 0x01010101u);
+        dg[hf][3] = (pl[1] >> 4) & M;
+        dg[hf][4] = (pl[1] >> 1) & M;
+        dg[hf][5] = ((pl[1] << 2) & 0x04040404u) | ((pl[0] >> 6) & 0x03030303u);
+        dg[hf][6] = (pl[0] >> 3) & M;
+        dg[hf][7] = pl[0] & M;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        uint32_t sl = 0, sh = 0;                     // digit i of the 8 elements, one per byte
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            sl |= ((fx[k] >> (21 - 3 * i)) & 7u) << (8 * k);
-            sh |= ((fx[k + 4] >> (21 - 3 * i)) & 7u) << (8 * k);
-        }
         // E5M2 of 0..7: 00 3C 40 42 44 45 46 47
-        const uint32_t lo = goq_perm(0x47464544u, 0x42403C00u, sl) | slo;
-        const uint32_t hi = goq_perm(0x47464544u, 0x42403C00u, sh) | shi;
+        const uint32_t lo = goq_perm(0x47464544u, 0x42403C00u, dg[0][i]) | slo;
+        const uint32_t hi = goq_perm(0x47464544u, 0x42403C00u, dg[1][i]) | shi;
         *reinterpret_cast<uint2 *>(dst + i * 32) = make_uint2(lo, hi);
     }
     if ((r & 5) == 0) st[(r & 2) | (r >> 3)] = (unsigned char)(emax + 110);
