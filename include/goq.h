@@ -56,7 +56,7 @@ enum {
 enum { GOQ_A16 = 0, GOQ_A8 = 1, GOQ_A4 = 2 };
 enum { GOQ_F16 = 0, GOQ_F32 = 1 };  /* output type                                      */
 
-#define GOQ_MAX_BATCH 8             /* problems per goq_gemv_batch call                 */
+#define GOQ_MAX_BATCH 8             /* problems per goq_gemv_batch / goq_gemm_batch call */
 
 /* library version, major * 1000 + minor */
 int goq_version(void);

@@ -37,7 +37,7 @@ static int check_shape(const char *fn, int bw, int64_t out, int64_t in)
 
 extern "C" {
 
-int goq_version(void) { return 1000; }
+int goq_version(void) { return 1001; }
 
 const char *goq_last_error(void) { return g_err; }
 
