@@ -30,7 +30,9 @@
  *       signs   u8  [out][in/8]     bit p = 1  <=>  eta of the p-th pair (ascending i) is -1
  *       c1, c2  u16 [out][in/128]   IEEE binary16 bit patterns
  *   - the packed buffer is opaque, position independent (it may be copied or saved) and holds
- *     exactly 4.0 (bw = 3) or 5.0 (bw = 4) bits per weight, rows padded to a multiple of 64.
+ *     exactly 4.0 (bw = 3) or 5.0 (bw = 4) bits per weight, rows padded to a multiple of 64.  Its
+ *     arrangement belongs to the library version that wrote it (goq_version): a saved buffer is
+ *     read back with goq_unpack of the same version, or repacked from the canonical arrays.
  */
 #ifndef GOQ_H
 #define GOQ_H
