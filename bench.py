@@ -110,6 +110,27 @@ def bench_gemv(args, shapes, bw, name):
     torch.cuda.synchronize()
     hot_ms = ev0.elapsed_time(ev1) / args.steps
 
+    # each matrix as a launch of its own (what a caller pays who does not batch the block): short
+    # launches, where the fixed cost of a launch shows
+    per_matrix = []
+    if len(shapes) > 1:
+        for k, (nm, o, i) in enumerate(shapes):
+            single = [binding.bind_gemv_batch(bw, goq.A16, binding.make_descs([(o, i, all_packed[c][k], xs[k], None, ys[k], goq.F32)]), stream)
+                      for c in range(copies)]
+            n1 = max(50, min(args.steps, 500))
+            for j in range(50):
+                single[j % copies]()
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            for j in range(n1):
+                single[j % copies]()
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            us = ev0.elapsed_time(ev1) / n1 * 1e3
+            nbytes = o * i * (bw + 1) / 8.0 + 2.0 * i + 4.0 * o
+            per_matrix.append({"name": nm, "out": o, "in": i, "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                               "kernel": gemv_kernel_name(bw, [(nm, o, i)])})
+
     value = alg_bytes / (wall_ms * 1e-3) / 1e9
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
     res = {
@@ -121,7 +142,9 @@ def bench_gemv(args, shapes, bw, name):
                    "weights": int(sum(o * i for _, o, i in shapes)), "algorithmic_bytes_per_step": int(alg_bytes),
                    "rotating_copies": copies, "launches_per_step": 1, "setup_s": round(setup_s, 1),
                    "settle_launches": args.settle,
-                   "cache_resident_GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1)},
+                   "cache_resident_GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1),
+                   "per_matrix_launches": per_matrix,
+                   "per_matrix_total_us": round(sum(m["us"] for m in per_matrix), 2) if per_matrix else None},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": gemv_kernel_name(bw, shapes), "avg_launch_us": round(dev_ms * 1e3, 3)},
