@@ -150,6 +150,11 @@ int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *de
 enum { GOQ_GEMV_AUTO = 0, GOQ_GEMV_STREAM = 1, GOQ_GEMV_ROWS = 2 };
 int goq_gemv_select(int kernel);
 
+/* What a goq_gemv_batch call with these shapes would launch under the current selection: *kernel
+ * receives GOQ_GEMV_STREAM or GOQ_GEMV_ROWS, *workgroups the grid size (both host pointers).
+ * Only out and in of the descriptors are read; nothing is launched and no device is touched. */
+int goq_gemv_plan(int bw, int act, int n, const goq_gemv_desc *descs, int *kernel, int *workgroups);
+
 /* Many-token layer output (Eq. 4), Y[tokens][out] = X[tokens][in] * W^T.
  *   act = GOQ_A16: X fp16, sx NULL; PoT codes are decoded to fp16 operands of the fp16 MFMA,
  *                  fp32 accumulation.

@@ -18,7 +18,7 @@ GEMV_AUTO, GEMV_STREAM, GEMV_ROWS = 0, 1, 2
 
 EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_ref_workspace_bytes",
            "goq_ref_coefficients", "goq_pack", "goq_unpack",
-           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemm", "goq_gemm_batch", "goq_gemm_folded"]
+           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemv_plan", "goq_gemm", "goq_gemm_batch", "goq_gemm_folded"]
 
 
 class GoqError(RuntimeError):
@@ -58,6 +58,7 @@ def lib():
         L.goq_gemv.argtypes = [vp, i, i, i64, i64, vp, vp, vp, vp, i]
         L.goq_gemv_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc)]
         L.goq_gemv_select.argtypes = [i]
+        L.goq_gemv_plan.argtypes = [i, i, i, ctypes.POINTER(_Desc), ctypes.POINTER(i), ctypes.POINTER(i)]
         L.goq_gemm.argtypes = [vp, i, i, i64, i64, i64, vp, vp, vp, vp, i, vp]
         L.goq_gemm_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_GemmDesc)]
         L.goq_gemm_folded.argtypes = [vp, i, i64, i64, i64, vp, vp, vp, i]
@@ -139,6 +140,16 @@ def make_descs(problems):
 
 def gemv_select(kernel):
     _check(lib().goq_gemv_select(kernel))
+
+
+def gemv_plan(bw, act, shapes):
+    """shapes: list of (out, in) -> (kernel, workgroups) a gemv_batch call of these layers would launch."""
+    arr = (_Desc * len(shapes))()
+    for d, (out, inn) in zip(arr, shapes):
+        d.out, d.in_ = out, inn
+    k, w = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().goq_gemv_plan(bw, act, len(arr), arr, ctypes.byref(k), ctypes.byref(w)))
+    return k.value, w.value
 
 
 def gemv_batch(bw, act, problems, stream=None):

@@ -143,6 +143,19 @@ int goq_gemv_select(int kernel)
     return GOQ_OK;
 }
 
+int goq_gemv_plan(int bw, int act, int n, const goq_gemv_desc *descs, int *kernel, int *workgroups)
+{
+    if (!descs || !kernel || !workgroups) return goq_set_error(GOQ_EINVAL, "goq_gemv_plan: NULL pointer");
+    if (n < 1 || n > GOQ_MAX_BATCH)
+        return goq_set_error(GOQ_ESHAPE, "goq_gemv_plan: n = %d must be in 1..%d", n, GOQ_MAX_BATCH);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4) return goq_set_error(GOQ_EINVAL, "goq_gemv_plan: bad activation type %d", act);
+    for (int i = 0; i < n; ++i) {
+        int rc = check_shape("goq_gemv_plan", bw, descs[i].out, descs[i].in);
+        if (rc) return rc;
+    }
+    return goq_gemv_plan_launch(n, descs, kernel, workgroups);
+}
+
 int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *descs)
 {
     if (!descs) return goq_set_error(GOQ_EINVAL, "goq_gemv_batch: descs is NULL");

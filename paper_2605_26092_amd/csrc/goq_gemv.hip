@@ -738,8 +738,32 @@ std::atomic<int> g_kernel{GOQ_GEMV_AUTO};
 
 void goq_gemv_set_kernel(int kernel) { g_kernel.store(kernel, std::memory_order_relaxed); }
 
+// Which kernel a launch of these problems takes under the current selection, and with how many
+// workgroups (host logic only).
+int goq_gemv_plan_launch(int n, const goq_gemv_desc *descs, int *kernel, int *workgroups)
+{
+    int64_t units = 0, blocks = 0, slices = 0;
+    for (int i = 0; i < n; ++i) {
+        const int64_t gn = descs[i].in / GOQ_N;
+        units += (goq_row_blocks(descs[i].out) + WAVES - 1) / WAVES * gn;
+        blocks += (descs[i].out + 15) / 16;
+        slices += (descs[i].out + 15) / 16 * gn;
+        if (units > 0x3fffffff || blocks > 0x3fffffff)
+            return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
+    }
+    const int which = g_kernel.load(std::memory_order_relaxed);
+    const bool rows = which == GOQ_GEMV_ROWS ||
+                      (which == GOQ_GEMV_AUTO && blocks <= ROWS_MAX_TILES && slices <= ROWS_MAX_SLICES);
+    *kernel = rows ? GOQ_GEMV_ROWS : GOQ_GEMV_STREAM;
+    *workgroups = rows ? (int)blocks : (int)(units < MAX_WG ? units : MAX_WG);
+    return GOQ_OK;
+}
+
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs)
 {
+    int kernel = 0, workgroups = 0;
+    const int rc = goq_gemv_plan_launch(n, descs, &kernel, &workgroups);
+    if (rc) return rc;
     GemvArgs a;
     a.n = n;
     int64_t total = 0;
@@ -756,24 +780,19 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
         P.rgroups = (P.rbn + WAVES - 1) / WAVES;
         P.begin = (int)total;
         total += (int64_t)P.rgroups * P.gn;
-        if (total > 0x3fffffff) return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
     }
     for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].begin = 0x7fffffff; }
     a.total = (int)total;
     // Small launches go to the row-owner kernel: one workgroup per 16 output rows.
     {
-        int64_t blocks = 0, slices = 0;
+        int64_t blocks = 0;
         for (int i = 0; i < n; ++i) {
             a.p[i].bb = (int)blocks;
             blocks += (descs[i].out + 15) / 16;
-            slices += (descs[i].out + 15) / 16 * a.p[i].gn;
         }
         for (int i = n; i < GOQ_MAX_BATCH; ++i) a.p[i].bb = 0x7fffffff;
-        const int which = g_kernel.load(std::memory_order_relaxed);
-        if (blocks > 0x3fffffff) return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
-        if (which == GOQ_GEMV_ROWS ||
-            (which == GOQ_GEMV_AUTO && blocks <= ROWS_MAX_TILES && slices <= ROWS_MAX_SLICES)) {
-            const int nb = (int)blocks;
+        if (kernel == GOQ_GEMV_ROWS) {
+            const int nb = workgroups;
             if (bw == 3 && act == GOQ_A16) return launch_rows<3, 0>(st, a, nb);
             if (bw == 3 && act == GOQ_A8) return launch_rows<3, 1>(st, a, nb);
             if (bw == 4 && act == GOQ_A8) return launch_rows<4, 1>(st, a, nb);
@@ -789,8 +808,7 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     if (!base) return goq_set_error(GOQ_EHIP, "goq_gemv: cannot resolve the scratch area on this device");
     a.scratch = base + ticket.fetch_add(1, std::memory_order_relaxed) % REGIONS;
     // two 512-thread workgroups per CU (4 wavefronts per SIMD)
-    int nwg = MAX_WG;
-    if (nwg > a.total) nwg = a.total;
+    const int nwg = workgroups;
     a.pq = a.total / nwg;
     a.pr = a.total % nwg;
     if (bw == 3 && act == GOQ_A16) return launch<3, 0>(st, a, nwg);

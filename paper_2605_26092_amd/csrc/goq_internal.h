@@ -20,6 +20,7 @@ int goq_launch_ref(hipStream_t st, int bw, int64_t tokens, int64_t out, int64_t 
                    double lambda, void *workspace, double *craw, uint16_t *c1, uint16_t *c2);
 int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs);
 void goq_gemv_set_kernel(int kernel);
+int goq_gemv_plan_launch(int n, const goq_gemv_desc *descs, int *kernel, int *workgroups);
 int goq_launch_gemm_folded(hipStream_t st, int bw, int64_t tokens, int64_t out, int64_t in, const void *packed,
                            const void *X, void *Y, int ytype);
 int goq_launch_gemm(hipStream_t st, int bw, int act, int n, const goq_gemm_desc *descs);

@@ -68,3 +68,29 @@ def test_host_side_argument_errors(goq):
     assert L.goq_gemv_batch(None, 3, 0, 0, None) == b.EINVAL
     with pytest.raises(goq.GoqError):
         goq.packed_bytes(3, 64, 64)
+
+
+def test_gemv_plan_follows_the_documented_choice(goq):
+    """Host logic of the automatic kernel choice (include/goq.h): at most 512 tiles of 16 rows and
+    24576 (tile, macro-block) pairs -> row-owner kernel, one workgroup per tile; else the streaming
+    kernel with min(units, 512) workgroups, a unit being 512 rows x one macro-block."""
+    b3 = lambda shapes: goq.gemv_plan(3, goq.A16, shapes)
+    assert b3([(4096, 4096)]) == (goq.GEMV_ROWS, 256)
+    assert b3([(8192, 4096)]) == (goq.GEMV_ROWS, 512)
+    assert b3([(8208, 128)]) == (goq.GEMV_STREAM, 17)                   # 513 tiles
+    assert b3([(8192, 8192)]) == (goq.GEMV_STREAM, 512)                 # 512 tiles x 64 = 32768 pairs
+    assert b3([(4096, 11008)]) == (goq.GEMV_ROWS, 256)                  # 256 x 86 = 22016 pairs
+    assert b3([(17, 128), (33, 256)]) == (goq.GEMV_ROWS, 2 + 3)
+    block = [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)]
+    assert b3(block) == (goq.GEMV_STREAM, 512)
+    assert goq.gemv_plan(4, goq.A8, [(4096, 4096)]) == (goq.GEMV_ROWS, 256)
+    try:
+        goq.gemv_select(goq.GEMV_STREAM)
+        assert b3([(4096, 4096)]) == (goq.GEMV_STREAM, 256)             # 8 row groups x 32 macro-blocks
+        assert b3([(100, 256)]) == (goq.GEMV_STREAM, 2)
+        goq.gemv_select(goq.GEMV_ROWS)
+        assert b3(block) == (goq.GEMV_ROWS, 4 * 256 + 2 * 688 + 256)
+    finally:
+        goq.gemv_select(goq.GEMV_AUTO)
+    with pytest.raises(goq.GoqError):
+        goq.gemv_plan(3, goq.A16, [(64, 100)])
