@@ -173,11 +173,10 @@ def bench_gemv(args, shapes, bw, name):
 
 
 def gemv_kernel_name(bw, shapes):
-    """The kernel the library's automatic choice launches for these layers (see goq_gemv_select in
-    include/goq.h): the row-owner kernel up to 512 16-row tiles and 24576 (tile, macro-block) pairs."""
-    tiles = sum((out + 15) // 16 for _, out, _ in shapes)
-    slices = sum((out + 15) // 16 * (inn // 128) for _, out, inn in shapes)
-    return ("gemv_rows_kernel<%d,0>" if tiles <= 512 and slices <= 24576 else "gemv_kernel<%d,0>") % bw
+    """The kernel the library launches for these layers in one goq_gemv_batch call (goq_gemv_plan)."""
+    import paper_2605_26092_amd as goq
+    kernel, _ = goq.gemv_plan(bw, goq.A16, [(out, inn) for _, out, inn in shapes])
+    return ("gemv_rows_kernel<%d,0>" if kernel == goq.GEMV_ROWS else "gemv_kernel<%d,0>") % bw
 
 
 def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, folded=False):
