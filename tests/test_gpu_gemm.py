@@ -149,14 +149,21 @@ def test_gemm_config3_sampled(oracle, bw, name, out, inn):
     assert e1 <= TOL, e1
 
 
-def test_gemm_config4_sampled(oracle):
-    """BASELINE config 4 (ViT-B fc1, 197 x 64 tokens, W3/A8): full GPU run with the partials
-    output, bit-exact on a seeded sample of 32 token rows."""
+@pytest.mark.parametrize("bw,act_name", [(3, "A8"), (3, "A4"), (4, "A8")])
+def test_gemm_config4_sampled(oracle, bw, act_name):
+    """BASELINE config 4 (ViT-B fc1, 197 x 64 tokens, W3/A8; also the W3/A4 and W4/A8 operating
+    points at the same size): full GPU run with the partials output, bit-exact on a seeded sample
+    of 32 token rows."""
     import paper_2605_26092_amd as goq
     tokens, out, inn = 197 * 64, 3072, 768
-    q = _quantize(oracle, 3, out, inn, 4)
-    Xq, sx = goq_inputs.activations_a8(tokens, inn, config_id=4, tensor_id=200)
-    Y, parts = _gemm(goq, q, Xq, goq.A8, goq.F32, sx_np=sx, want_partials=True)
+    print("gemm config4 bw=%d %s" % (bw, act_name), flush=True)
+    q = _quantize(oracle, bw, out, inn, 4)
+    if act_name == "A8":
+        Xq, sx = goq_inputs.activations_a8(tokens, inn, config_id=4, tensor_id=200)
+        Y, parts = _gemm(goq, q, Xq, goq.A8, goq.F32, sx_np=sx, want_partials=True)
+    else:
+        Xq, sx = goq_inputs.activations_int(tokens, inn, 4, config_id=4, tensor_id=200)
+        Y, parts = _gemm(goq, q, goq_inputs.pack_int4(Xq), goq.A4, goq.F32, sx_np=sx, want_partials=True)
     rows = np.sort(goq_inputs.rng(4, 999).choice(tokens, size=32, replace=False))
     ref, rp = oracle.gemm_a8(q, Xq[rows], sx[rows], threads=8, want_partials=True)
     idx = gu.torch_cuda().from_numpy(rows).cuda()
