@@ -40,7 +40,43 @@ def gemv_bytes(bw, shapes, ybytes=4):
     return tot
 
 
+def _event_pairs(torch, n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _stats_us(per_step_us):
+    a = np.sort(np.asarray(per_step_us, dtype=np.float64))
+    return {"mean": round(float(a.mean()), 3), "median": round(float(np.median(a)), 3), "min": round(float(a[0]), 3)}
+
+
+def quantize_block_on_device(goq, torch, shapes, bw, config_id, dev):
+    """Seeded fp16 weights -> goq_quantize (GEO mode, on the device) -> goq_pack.  Returns the packed
+    buffers' sizes, the packed tensors and the host weights (for the cpu_baseline leg)."""
+    packed, host_w = [], []
+    for idx, (_, out, inn) in enumerate(shapes):
+        w = goq_inputs.weights(out, inn, config_id=config_id, tensor_id=idx)
+        host_w.append(w)
+        wd = torch.from_numpy(w.view(np.int16)).to(dev)
+        codes = torch.empty((out, inn), dtype=torch.uint8, device=dev)
+        pat = torch.empty((out, inn // 8), dtype=torch.uint8, device=dev)
+        sg = torch.empty((out, inn // 8), dtype=torch.uint8, device=dev)
+        c1 = torch.empty((out, inn // 128), dtype=torch.int16, device=dev)
+        c2 = torch.empty((out, inn // 128), dtype=torch.int16, device=dev)
+        goq.quantize(bw, out, inn, wd, codes, pat, sg, c1, c2)
+        pk = torch.empty(goq.packed_bytes(bw, out, inn), dtype=torch.uint8, device=dev)
+        goq.pack(bw, out, inn, codes, pat, sg, c1, c2, pk)
+        torch.cuda.synchronize()
+        packed.append(pk)
+        del wd, codes, pat, sg, c1, c2
+    return packed, host_w
+
+
 def bench_gemv(args, shapes, bw, name):
+    """Batch-1 workloads.  A step = one pass of the whole path over one block (all its matrices).
+    Steps are issued as goq_gemv_stream launches of up to `stream_blocks` blocks -- e.g. the 32
+    decoder blocks of LLaMA-2-7B: one token through the model's projections -- every block with
+    packed weights of its own, so one launch streams stream_blocks x (block bytes) of distinct
+    weights from HBM.  The one-block-per-launch figure (goq_gemv_batch) is reported beside it."""
     import torch
     import paper_2605_26092_amd as goq
     from paper_2605_26092_amd import binding
@@ -49,112 +85,190 @@ def bench_gemv(args, shapes, bw, name):
     torch.cuda.set_device(dev)
     alg_bytes = gemv_bytes(bw, shapes)
     weight_bytes = sum(goq.packed_bytes(bw, o, i) for _, o, i in shapes)
-    copies = max(2, int(np.ceil((1 << 30) / weight_bytes)))
+    # blocks per launch: the 32 decoder blocks of LLaMA-2-7B; otherwise about 3 GiB of distinct weights
+    NB = args.stream_blocks if args.stream_blocks > 0 else (
+        32 if [s[1:] for s in shapes] == [s[1:] for s in goq_inputs.LLAMA2_7B_BLOCK]
+        else max(8, min(128, int(np.ceil((3 << 30) / weight_bytes)))))
+    copies = NB
 
     t_setup = time.time()
-    packed0, xs, ys, canon = [], [], [], []
+    packed0, host_w = quantize_block_on_device(goq, torch, shapes, bw, 2, dev)
+    # all copies in one allocation (block after block), so that the read probe can stream the very
+    # bytes a launch streams
+    big = torch.empty(copies * weight_bytes, dtype=torch.uint8, device=dev)
+    all_packed, off = [], 0
+    for c in range(copies):
+        blk = []
+        for pk in packed0:
+            view = big[off:off + pk.numel()]
+            view.copy_(pk)
+            blk.append(view)
+            off += pk.numel()
+        all_packed.append(blk)
+    xs, ys = [], []
     for idx, (nm, out, inn) in enumerate(shapes):
-        q = goq_inputs.canonical_random(bw, out, inn, config_id=2, tensor_id=300 + idx)
-        canon.append(q)
-        pk = torch.empty(goq.packed_bytes(bw, out, inn), dtype=torch.uint8, device=dev)
-        d = [torch.from_numpy(q[k].view(np.int16) if q[k].dtype == np.uint16 else q[k]).to(dev)
-             for k in ("codes", "pattern", "signs", "c1", "c2")]
-        goq.pack(bw, out, inn, *d, pk)
-        torch.cuda.synchronize()
-        del d
-        packed0.append(pk)
         x = goq_inputs.activations_a16(1, inn, config_id=2, tensor_id=100 + idx, outlier_frac=0.01)
         xs.append(torch.from_numpy(x.reshape(-1)).to(dev))
-        ys.append(torch.zeros(out, dtype=torch.float32, device=dev))
-    all_packed = [packed0] + [[p.clone() for p in packed0] for _ in range(copies - 1)]
-    descs = [binding.make_descs([(o, i, all_packed[c][k], xs[k], None, ys[k], goq.F32)
-                                 for k, (_, o, i) in enumerate(shapes)]) for c in range(copies)]
+    ys = [[torch.zeros(out, dtype=torch.float32, device=dev) for _, out, _ in shapes] for _ in range(copies)]
+    stream = torch.cuda.current_stream()
+
+    def problems(c):
+        return [(o, i, all_packed[c][k], xs[k], None, ys[c][k], goq.F32) for k, (_, o, i) in enumerate(shapes)]
+
+    ws = torch.empty(goq.gemv_workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+    ws = ws[(-ws.data_ptr()) % 256:][:goq.gemv_workspace_bytes()]
+    goq.gemv_workspace_init(ws, stream=stream)
+    tables = {}
+
+    def stream_launch(nblocks):
+        """a bound goq_gemv_stream launch over the first `nblocks` copies"""
+        if nblocks not in tables:
+            probs = [p for c in range(nblocks) for p in problems(c)]
+            th, nbytes = goq.gemv_stream_table(bw, goq.A16, probs)
+            import ctypes
+            raw = np.frombuffer((ctypes.c_ubyte * nbytes).from_address(ctypes.addressof(th)), dtype=np.uint8).copy()
+            td = torch.from_numpy(raw).to(dev)
+            tables[nblocks] = (th, td, binding.bind_gemv_stream(th, td, ws, stream))
+        return tables[nblocks][2]
+
+    def plan(nsteps):
+        """launches (blocks each) that make up nsteps steps"""
+        return [NB] * (nsteps // NB) + ([nsteps % NB] if nsteps % NB else [])
+
+    for nb in set(plan(args.steps) + plan(args.warmup) + [NB]):
+        stream_launch(nb)
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
-    stream = torch.cuda.current_stream()
-
-    launches = [binding.bind_gemv_batch(bw, goq.A16, d, stream) for d in descs]
-
-    def step(i):
-        launches[i % copies]()
-
-    # clock settle (part of set-up, untimed): the launches are tens of microseconds long, so the
-    # W warm-up steps alone end before the GPU's clock governor has reacted to the load
-    for i in range(args.settle):
-        step(i)
+    # clock settle (part of set-up, untimed, echoed as effective warm-up): short runs end before the
+    # GPU's clock governor has reacted to the load
+    settle_steps = 0
+    t_end = time.perf_counter() + args.settle_ms * 1e-3
+    while time.perf_counter() < t_end:
+        stream_launch(NB)()
+        settle_steps += NB
+        if settle_steps % (8 * NB) == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
-    for i in range(args.warmup):
-        step(i)
+    for nb in plan(args.warmup):
+        stream_launch(nb)()
     torch.cuda.synchronize()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
+
+    timed = plan(args.steps)
+    ev = _event_pairs(torch, len(timed) + 1)
     t0 = time.perf_counter()
-    ev0.record(stream)
-    for i in range(args.steps):
-        step(args.warmup + i)
-    ev1.record(stream)
+    ev[0].record(stream)
+    for j, nb in enumerate(timed):
+        stream_launch(nb)()
+        ev[j + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / args.steps
-    dev_ms = ev0.elapsed_time(ev1) / args.steps
+    dev_ms = ev[0].elapsed_time(ev[-1]) / args.steps
+    per_step_us = [ev[j].elapsed_time(ev[j + 1]) * 1e3 / nb for j, nb in enumerate(timed)]
+    full_us = [ev[j].elapsed_time(ev[j + 1]) * 1e3 for j, nb in enumerate(timed) if nb == NB]
 
-    # cache-resident figure (same copy every step), labelled, not the headline
-    for i in range(10):
-        launches[0]()
+    # one block per launch (goq_gemv_batch), rotating over the copies: what a caller pays who launches
+    # block by block
+    single = [binding.bind_gemv_batch(bw, goq.A16, binding.make_descs(problems(c)), stream) for c in range(copies)]
+    n1 = max(64, min(args.steps, 2000))
+    for j in range(max(200, args.warmup)):
+        single[j % copies]()
     torch.cuda.synchronize()
-    ev0.record(stream)
-    for i in range(args.steps):
-        launches[0]()
-    ev1.record(stream)
+    chunk = 16                                           # events every 16 launches: median / min of those
+    evs = _event_pairs(torch, n1 // chunk + 1)
+    evs[0].record(stream)
+    for j in range(n1 // chunk * chunk):
+        single[j % copies]()
+        if j % chunk == chunk - 1:
+            evs[j // chunk + 1].record(stream)
     torch.cuda.synchronize()
-    hot_ms = ev0.elapsed_time(ev1) / args.steps
+    single_us = [evs[j].elapsed_time(evs[j + 1]) * 1e3 / chunk for j in range(n1 // chunk)]
+    single_mean_us = evs[0].elapsed_time(evs[-1]) * 1e3 / (n1 // chunk * chunk)
+    # the same copy every launch: cache-resident figure, labelled, not the headline
+    for j in range(20):
+        single[0]()
+    torch.cuda.synchronize()
+    evs[0].record(stream)
+    for j in range(n1):
+        single[0]()
+    evs[1].record(stream)
+    torch.cuda.synchronize()
+    hot_us = evs[0].elapsed_time(evs[1]) * 1e3 / n1
 
-    # each matrix as a launch of its own (what a caller pays who does not batch the block): short
-    # launches, where the fixed cost of a launch shows
+    # each matrix as a launch of its own
     per_matrix = []
     if len(shapes) > 1:
         for k, (nm, o, i) in enumerate(shapes):
-            single = [binding.bind_gemv_batch(bw, goq.A16, binding.make_descs([(o, i, all_packed[c][k], xs[k], None, ys[k], goq.F32)]), stream)
-                      for c in range(copies)]
-            n1 = max(50, min(args.steps, 500))
+            one = [binding.bind_gemv_batch(bw, goq.A16, binding.make_descs([problems(c)[k]]), stream) for c in range(copies)]
+            n2 = max(50, min(args.steps, 500))
             for j in range(50):
-                single[j % copies]()
+                one[j % copies]()
             torch.cuda.synchronize()
-            ev0.record(stream)
-            for j in range(n1):
-                single[j % copies]()
-            ev1.record(stream)
+            evs[0].record(stream)
+            for j in range(n2):
+                one[j % copies]()
+            evs[1].record(stream)
             torch.cuda.synchronize()
-            us = ev0.elapsed_time(ev1) / n1 * 1e3
+            us = evs[0].elapsed_time(evs[1]) / n2 * 1e3
             nbytes = o * i * (bw + 1) / 8.0 + 2.0 * i + 4.0 * o
             per_matrix.append({"name": nm, "out": o, "in": i, "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
                                "kernel": gemv_kernel_name(bw, [(nm, o, i)])})
 
-    value = alg_bytes / (wall_ms * 1e-3) / 1e9
+    # measured ceiling: a pure read stream over the bytes one full launch streams
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    nprobe = NB * weight_bytes
+    for _ in range(2):
+        goq.read_probe(big, nprobe, sink, stream=stream)
+    torch.cuda.synchronize()
+    pe = _event_pairs(torch, 6)
+    pe[0].record(stream)
+    for j in range(5):
+        goq.read_probe(big, nprobe, sink, stream=stream)
+        pe[j + 1].record(stream)
+    torch.cuda.synchronize()
+    probe_gbs = [nprobe / (pe[j].elapsed_time(pe[j + 1]) * 1e-3) / 1e9 for j in range(5)]
+
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    launch_us = float(np.mean(full_us)) if full_us else dev_ms * 1e3 * timed[0]
     res = {
         "metric": "PoT GEMV GB/s (% HBM peak) and GEMM TOPS (% MFMA peak), LLaMA-2-7B shapes",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "value": round(achieved, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dev_ms, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 x as eight 3-bit E5M2 digits of 24-bit block fixed point, E5M2 PoT weights, fp8 MFMA, f32 accumulate",
+        "data": "synthetic",
         "config": {"workload": name, "bw": bw, "act": "A16", "group": 128, "matrices": len(shapes),
                    "weights": int(sum(o * i for _, o, i in shapes)), "algorithmic_bytes_per_step": int(alg_bytes),
-                   "rotating_copies": copies, "launches_per_step": 1, "setup_s": round(setup_s, 1),
-                   "settle_launches": args.settle,
-                   "cache_resident_GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1),
+                   "weights_from": "seeded fp16 weights quantised by goq_quantize (GEO mode) on the device",
+                   "launch": "goq_gemv_stream: up to %d blocks (steps) per launch, each block with packed weights of its own" % NB,
+                   "stream_blocks": NB, "distinct_packed_bytes": int(copies * weight_bytes),
+                   "launches_timed": len(timed), "blocks_per_launch": timed if len(timed) <= 4 else [timed[0], "...", timed[-1]],
+                   "clock": "HIP events on the launch stream, first launch to last (value, ms_per_step, roofline use it)",
+                   "wall_ms_per_step": round(wall_ms, 6),
+                   "step_us": _stats_us(per_step_us),
+                   "setup_s": round(setup_s, 1), "settle_ms": args.settle_ms,
+                   "effective_warmup_steps": settle_steps + args.warmup,
+                   "single_block_launch": {"entry": "goq_gemv_batch, one block per launch, rotating over the copies",
+                                           "kernel": gemv_kernel_name(bw, shapes), "us": _stats_us(single_us),
+                                           "GBps": round(alg_bytes / single_mean_us / 1e3, 1),
+                                           "frac": round(alg_bytes / single_mean_us / 1e3 / HBM_PEAK_GBS, 4),
+                                           "cache_resident_GBps": round(alg_bytes / hot_us / 1e3, 1)},
                    "per_matrix_launches": per_matrix,
                    "per_matrix_total_us": round(sum(m["us"] for m in per_matrix), 2) if per_matrix else None},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": gemv_kernel_name(bw, shapes), "avg_launch_us": round(dev_ms * 1e3, 3)},
+                     "kernel": "gemv_stream_kernel<%d,0>" % bw, "avg_launch_us": round(launch_us, 3),
+                     "units_per_launch": "%d blocks" % (NB if full_us else timed[0]),
+                     "peak_measured": {"value": round(max(probe_gbs), 1), "mean": round(float(np.mean(probe_gbs)), 1), "unit": "GB/s",
+                                       "what": "goq_read_probe: pure nontemporal read stream over the %d bytes one full launch streams, 512 x 512 threads" % nprobe}},
     }
     # HBM traffic per launch from the committed counter runs (FETCH_SIZE + WRITE_SIZE, scaled), if present
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json.txt")) as fh:
-            t = json.load(fh)["gemv_kernel<3,0>"]
-            if t["workload"] == name:
+            t = json.load(fh)["gemv_stream_kernel<%d,0>" % bw]
+            if t["workload"] == name and t["stream_blocks"] == NB:
                 res["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
+                res["roofline"]["traffic_source"] = t["source"]
     except (OSError, KeyError, ValueError):
         pass
     if args.traffic_ref:
@@ -168,7 +282,7 @@ def bench_gemv(args, shapes, bw, name):
         del src, dst
     if args.gemm_tokens > 0:
         res["gemm"] = bench_gemm_block(args, shapes, bw, goq.A16, packed0, args.gemm_tokens)
-    res["cpu_baseline"] = cpu_baseline_gemv(canon, shapes, bw, alg_bytes) if not args.no_cpu else None
+    res["cpu_baseline"] = cpu_baseline_gemv(host_w, shapes, bw, alg_bytes) if not args.no_cpu else None
     return res
 
 
@@ -456,10 +570,12 @@ def cpu_baseline_gemm(canon, shapes, bw, act_name, tokens):
             % (reps, slab, out, inn, el)}
 
 
-def cpu_baseline_gemv(canon, shapes, bw, alg_bytes):
-    """The oracle, untuned, on the host cores: the same block of GEMVs."""
+def cpu_baseline_gemv(host_w, shapes, bw, alg_bytes):
+    """The oracle, untuned, on the host cores: the same block of GEMVs (weights quantised by the
+    oracle's own GEO quantizer first, untimed)."""
     from oracle import goq_oracle as O
     threads = min(O.max_threads(), os.cpu_count() or 1)
+    canon = [O.quantize_geo(bw, w, threads=threads) for w in host_w]
     xs = [goq_inputs.activations_a16(1, inn, config_id=2, tensor_id=100 + k, outlier_frac=0.01)
           for k, (_, _, inn) in enumerate(shapes)]
     reps, t0 = 0, time.perf_counter()
@@ -471,16 +587,18 @@ def cpu_baseline_gemv(canon, shapes, bw, alg_bytes):
         if el > 10.0 or reps >= 20:
             break
     return {"value": round(alg_bytes * reps / el / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "%d pass(es) of the full block (all 7 GEMVs, all rows), %.1f s" % (reps, el)}
+            "sample": "%d pass(es) of the full block (all %d GEMVs, all rows), %.1f s" % (reps, len(shapes), el)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--settle", type=int, default=3000,
-                    help="GEMV workloads: untimed launches before the warm-up that let the GPU clocks settle")
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="GEMV workloads: milliseconds of untimed launches before the warm-up that let the GPU clocks settle")
+    ap.add_argument("--stream-blocks", type=int, default=0,
+                    help="GEMV workloads: blocks per goq_gemv_stream launch (0 = by workload: 32 for the 7B block)")
     ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3", "c3_gemm_folded", "c2_gemv_w4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",

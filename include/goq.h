@@ -59,6 +59,7 @@ enum { GOQ_A16 = 0, GOQ_A8 = 1, GOQ_A4 = 2 };
 enum { GOQ_F16 = 0, GOQ_F32 = 1 };  /* output type                                      */
 
 #define GOQ_MAX_BATCH 8             /* problems per goq_gemv_batch / goq_gemm_batch call */
+#define GOQ_MAX_STREAM 65536        /* problems per goq_gemv_stream table               */
 
 /* library version, major * 1000 + minor */
 int goq_version(void);
@@ -66,7 +67,9 @@ int goq_version(void);
 /* text of the calling thread's last error (host pointer, valid until the thread's next call) */
 const char *goq_last_error(void);
 
-/* size in bytes of the packed buffer of a [out][in] layer.  *bytes is a host pointer. */
+/* size in bytes of the packed buffer of a [out][in] layer: the stored representation of Sec. 3.3
+ * item 3 (code bits + 6 metadata bits per 8 weights + two fp16 coefficients per 128 weights) with
+ * rows padded to a multiple of 64.  *bytes is a host pointer. */
 int goq_packed_bytes(int bw, int64_t out, int64_t in, size_t *bytes);
 
 /* Data-free GEO-mode quantizer (Sec. 3.2 - 3.4) on the device: fp16 weights w [out][in] (IEEE
@@ -104,7 +107,7 @@ int goq_pack(void *stream, int bw, int64_t out, int64_t in,
              const uint8_t *codes, const uint8_t *pattern, const uint8_t *signs,
              const uint16_t *c1, const uint16_t *c2, void *packed);
 
-/* Inverse of goq_pack (test hook): packed buffer -> canonical arrays. */
+/* Inverse of goq_pack (test hook): packed buffer -> the canonical arrays of Sec. 3.3 item 3. */
 int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed,
                uint8_t *codes, uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
 
@@ -117,10 +120,15 @@ int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed
  *   run on the 8-bit-float matrix instruction against x written as block fixed point (24 bits
  *   below the largest exponent of each 32-activation block: exact for int8 x, and for fp16 x up
  *   to a truncation at 2^-24 of the block maximum), accumulate in fp32; coefficients are applied
- *   per slab in fp32.  Results are deterministic (no floating-point atomics).  Row groups split
- *   over several workgroups are combined through a library-owned scratch area on the device
- *   (16 MiB, 8 regions handed out round-robin): at most 8 goq_gemv / goq_gemv_batch launches
- *   may be in flight at the same time on one device. */
+ *   per slab in fp32.  Results are deterministic (no floating-point atomics).  x must be finite
+ *   (Inf / NaN inputs give unspecified finite or non-finite outputs).
+ *   Row groups split over several workgroups are combined through one of the library's 8 static
+ *   scratch regions on the device (2.1 MB each), one region per stream: launches on one stream run
+ *   one after the other and may follow each other without limit.  A 9th stream takes over the
+ *   region of the least recently used stream after waiting ON THE HOST until that stream has
+ *   drained (the one case in which a call of this library blocks); if one of the two streams is
+ *   being captured the call returns GOQ_EUNSUPPORTED instead.  A captured graph bakes the region
+ *   of its capture stream in: replay it on that stream only, or capture goq_gemv_batch_ws. */
 int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in,
              const void *packed, const void *x, const float *sx, void *y, int ytype);
 
@@ -136,9 +144,63 @@ typedef struct goq_gemv_desc {
 } goq_gemv_desc;
 int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *descs);
 
+/* goq_gemv_batch for callers that cannot allocate and want no library-side state: the
+ * workspace for split row groups is the caller's.  For: launches under HIP graph capture that are
+ * replayed on any stream, serving loops with more than 8 streams in flight, harnesses that forbid
+ * library-owned device state.  workspace: goq_gemv_workspace_bytes() bytes of device memory,
+ * 256-byte aligned, zero-filled once by goq_gemv_workspace_init (a kernel launch on `stream`, no
+ * memset node) before its first use; every completed launch leaves it ready for the next.  One
+ * workspace serves one launch at a time: launches that share it must be ordered (same stream, or
+ * events).  The workspace size does not depend on the problem sizes.  Results are bit-identical
+ * to goq_gemv_batch. */
+int goq_gemv_workspace_bytes(size_t *bytes);                 /* *bytes is a host pointer */
+int goq_gemv_workspace_init(void *stream, void *workspace);
+int goq_gemv_batch_ws(void *stream, int bw, int act, int n, const goq_gemv_desc *descs, void *workspace);
+
+/* A whole stream of batch-1 layers in ONE launch (Eq. 4 with one token, for every layer of the
+ * stream): e.g. all projections of all decoder blocks of a model.  The units (512 output rows x
+ * one 128-wide slab) of all n <= GOQ_MAX_STREAM problems form one sequence that is cut into equal
+ * contiguous pieces, one per workgroup, so start-up and tail of the launch are paid once per
+ * stream instead of once per block.  The problems are independent: the library orders nothing
+ * between them (x of every problem must be ready before the launch).
+ *   goq_gemv_stream_table writes the problem table (goq_gemv_stream_table_bytes(n) bytes) into a
+ *   HOST buffer, 8-byte aligned; the caller copies those bytes to device memory (16-byte aligned)
+ *   and passes both copies to goq_gemv_stream: the host copy tells the library the launch shape,
+ *   the device copy feeds the kernel.  The table holds the descriptors' device pointers: it stays
+ *   valid as long as they do.  All problems share bw and act.
+ *   workspace: as for goq_gemv_batch_ws.
+ * A stream of the problems of one goq_gemv_batch call gives that call's streaming-kernel results
+ * bit for bit; in general the split points, hence the fp32 summation order, depend on the stream. */
+int goq_gemv_stream_table_bytes(int n, size_t *bytes);       /* *bytes is a host pointer */
+int goq_gemv_stream_table(int bw, int act, int n, const goq_gemv_desc *descs, void *table /* host */);
+int goq_gemv_stream(void *stream, const void *table_host, const void *table_dev, void *workspace);
+
+/* Test hook: measures, on the device, the two properties of the 8-bit-float matrix instruction
+ * that the exactness of the batch-1 path (Eq. 4 with integer activations: exact slab sums)
+ * rests on.  report: 17 int32 in device memory.
+ *   report[0]        depth of the fixed-point grid on which the products of 8 consecutive k are
+ *                    added, in binary places below the largest product (the library needs >= 10:
+ *                    3-bit digits against powers of two 2^0 .. 2^-7; gfx950 gives 13)
+ *   report[1 + 4 Q + i], Q = 0..3, i = 0..3: bit b set <=> the block scale supplied by lane
+ *                    (row, Q) applies to k = 32 i + b of that A row.  The library assumes
+ *                    k-groups 2 (Q % 2) and 2 (Q % 2) + 1 (i.e. i), bits 16 (Q / 2) .. + 15. */
+int goq_mfma_probe(void *stream, int32_t *report);
+
+/* Measurement hooks: the ceilings of this device as a kernel of this library's launch shape sees
+ * them, reported by bench.py beside the nominal peaks (they compute nothing of the method).
+ *   goq_read_probe       streams buf [bytes] (device, 16-byte aligned, >= 4 MiB) once with
+ *                        nontemporal 16-byte loads, 512 workgroups of 512 threads, one contiguous
+ *                        piece each: the read rate a batch-1 launch of that size could reach at best.
+ *   goq_mfma_rate_probe  `workgroups` x 4 wavefronts, each issuing iters x 4 matrix instructions
+ *                        on four accumulator chains and nothing else.  kind 0: fp16 32x32x16,
+ *                        1: int8 32x32x32, 2: 8-bit float 16x16x128.  *ops (host) receives the
+ *                        operations of the launch (2 per multiply-add).
+ * sink: 4 bytes of device memory (written only if the data happen to hash to a magic value). */
+int goq_read_probe(void *stream, const void *buf, size_t bytes, uint32_t *sink);
+int goq_mfma_rate_probe(void *stream, int kind, int workgroups, int iters, float *sink, double *ops);
+
 /* Which of the two batch-1 kernels goq_gemv / goq_gemv_batch launch (process-wide, takes effect
- * with the next call; both kernels compute the same sums, H2..H6 of Sec. 3.3, and both accept
- * every shape):
+ * with the next call; both kernels compute the same sums of Eq. 4 and both accept every shape):
  *   GOQ_GEMV_AUTO   (default) by size: launches of at most 512 tiles of 16 output rows (each
  *                   problem's rows rounded up to 16) and at most 24576 (tile, macro-block)
  *                   pairs -- 48 Mi weights -- go to the row-owner kernel, everything else streams;

@@ -18,7 +18,8 @@ GEMV_AUTO, GEMV_STREAM, GEMV_ROWS = 0, 1, 2
 
 EXPORTS = ["goq_version", "goq_last_error", "goq_packed_bytes", "goq_quantize", "goq_ref_workspace_bytes",
            "goq_ref_coefficients", "goq_pack", "goq_unpack",
-           "goq_gemv", "goq_gemv_batch", "goq_gemv_select", "goq_gemv_plan", "goq_gemm", "goq_gemm_batch", "goq_gemm_folded"]
+           "goq_gemv", "goq_gemv_batch", "goq_gemv_workspace_bytes", "goq_gemv_workspace_init", "goq_gemv_batch_ws",
+           "goq_gemv_stream_table_bytes", "goq_gemv_stream_table", "goq_gemv_stream", "goq_mfma_probe", "goq_read_probe", "goq_mfma_rate_probe", "goq_gemv_select", "goq_gemv_plan", "goq_gemm", "goq_gemm_batch", "goq_gemm_folded"]
 
 
 class GoqError(RuntimeError):
@@ -45,6 +46,9 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             raise ImportError("libgoq.so is not built: run `python -m paper_2605_26092_amd.build` "
                               "(or __graft_entry__.build()) first; there is no fallback path")
+        # torch first: libgoq.so binds to the HIP runtime already in the process (same soname), and
+        # that must be the one that owns the caller's tensors and streams, i.e. the one torch ships
+        import torch  # noqa: F401
         L = ctypes.CDLL(_LIB_PATH)
         vp, i, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         L.goq_version.restype = i
@@ -57,6 +61,15 @@ def lib():
         L.goq_unpack.argtypes = [vp, i, i64, i64, vp, vp, vp, vp, vp, vp]
         L.goq_gemv.argtypes = [vp, i, i, i64, i64, vp, vp, vp, vp, i]
         L.goq_gemv_batch.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc)]
+        L.goq_gemv_workspace_bytes.argtypes = [ctypes.POINTER(ctypes.c_size_t)]
+        L.goq_gemv_workspace_init.argtypes = [vp, vp]
+        L.goq_gemv_batch_ws.argtypes = [vp, i, i, i, ctypes.POINTER(_Desc), vp]
+        L.goq_gemv_stream_table_bytes.argtypes = [i, ctypes.POINTER(ctypes.c_size_t)]
+        L.goq_gemv_stream_table.argtypes = [i, i, i, ctypes.POINTER(_Desc), vp]
+        L.goq_gemv_stream.argtypes = [vp, vp, vp, vp]
+        L.goq_mfma_probe.argtypes = [vp, vp]
+        L.goq_read_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.goq_mfma_rate_probe.argtypes = [vp, i, i, i, vp, ctypes.POINTER(ctypes.c_double)]
         L.goq_gemv_select.argtypes = [i]
         L.goq_gemv_plan.argtypes = [i, i, i, ctypes.POINTER(_Desc), ctypes.POINTER(i), ctypes.POINTER(i)]
         L.goq_gemm.argtypes = [vp, i, i, i64, i64, i64, vp, vp, vp, vp, i, vp]
@@ -138,6 +151,21 @@ def make_descs(problems):
     return arr
 
 
+def mfma_probe(report, stream=None):
+    _check(lib().goq_mfma_probe(_stream(stream), _ptr(report)))
+
+
+def read_probe(buf, nbytes, sink, stream=None):
+    _check(lib().goq_read_probe(_stream(stream), _ptr(buf), nbytes, _ptr(sink)))
+
+
+def mfma_rate_probe(kind, workgroups, iters, sink, stream=None):
+    """-> operations (2 per multiply-add) of the launch."""
+    ops = ctypes.c_double(0.0)
+    _check(lib().goq_mfma_rate_probe(_stream(stream), kind, workgroups, iters, _ptr(sink), ctypes.byref(ops)))
+    return ops.value
+
+
 def gemv_select(kernel):
     _check(lib().goq_gemv_select(kernel))
 
@@ -155,6 +183,47 @@ def gemv_plan(bw, act, shapes):
 def gemv_batch(bw, act, problems, stream=None):
     arr = problems if isinstance(problems, ctypes.Array) else make_descs(problems)
     _check(lib().goq_gemv_batch(_stream(stream), bw, act, len(arr), arr))
+
+
+def gemv_workspace_bytes():
+    n = ctypes.c_size_t(0)
+    _check(lib().goq_gemv_workspace_bytes(ctypes.byref(n)))
+    return n.value
+
+
+def gemv_workspace_init(workspace, stream=None):
+    _check(lib().goq_gemv_workspace_init(_stream(stream), _ptr(workspace)))
+
+
+def gemv_batch_ws(bw, act, problems, workspace, stream=None):
+    arr = problems if isinstance(problems, ctypes.Array) else make_descs(problems)
+    _check(lib().goq_gemv_batch_ws(_stream(stream), bw, act, len(arr), arr, _ptr(workspace)))
+
+
+def gemv_stream_table(bw, act, problems):
+    """problems (list of (out, in, packed, x, sx, y, ytype) or a ctypes array from make_descs) -> the
+    problem table as a host buffer (a ctypes char array); the caller copies it to the device."""
+    arr = problems if isinstance(problems, ctypes.Array) else make_descs(problems)
+    n = ctypes.c_size_t(0)
+    _check(lib().goq_gemv_stream_table_bytes(len(arr), ctypes.byref(n)))
+    buf = (ctypes.c_uint64 * ((n.value + 7) // 8))()
+    _check(lib().goq_gemv_stream_table(bw, act, len(arr), arr, ctypes.addressof(buf)))
+    return buf, n.value
+
+
+def gemv_stream(table_host, table_dev, workspace, stream=None):
+    _check(lib().goq_gemv_stream(_stream(stream), ctypes.addressof(table_host), _ptr(table_dev), _ptr(workspace)))
+
+
+def bind_gemv_stream(table_host, table_dev, workspace, stream=None):
+    """A zero-argument callable that launches goq_gemv_stream on pre-marshalled arguments."""
+    fn, s, th, td, ws = lib().goq_gemv_stream, _stream(stream), ctypes.addressof(table_host), _ptr(table_dev), _ptr(workspace)
+
+    def call():
+        rc = fn(s, th, td, ws)
+        if rc:
+            _check(rc)
+    return call
 
 
 def bind_gemv_batch(bw, act, descs, stream=None):

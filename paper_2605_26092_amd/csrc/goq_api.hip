@@ -132,7 +132,31 @@ int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in, const void 
     d.out = out; d.in = in; d.packed = packed; d.x = x; d.sx = sx; d.y = y; d.ytype = ytype;
     int rc = check_gemv_desc("goq_gemv", bw, act, d);
     if (rc) return rc;
-    return goq_launch_gemv((hipStream_t)stream, bw, act, 1, &d);
+    return goq_launch_gemv((hipStream_t)stream, bw, act, 1, &d, nullptr);
+}
+
+int goq_mfma_probe(void *stream, int32_t *report)
+{
+    if (!report || misaligned(report, 4)) return goq_set_error(GOQ_EINVAL, "goq_mfma_probe: report must be a 4-byte aligned device pointer");
+    return goq_launch_mfma_probe((hipStream_t)stream, report);
+}
+
+int goq_read_probe(void *stream, const void *buf, size_t bytes, uint32_t *sink)
+{
+    if (!buf || !sink || misaligned(buf, 16) || misaligned(sink, 4))
+        return goq_set_error(GOQ_EINVAL, "goq_read_probe: buf must be 16-byte aligned, sink 4-byte");
+    if (bytes < (size_t)512 * 512 * 16 || bytes % 16)
+        return goq_set_error(GOQ_ESHAPE, "goq_read_probe: bytes must be a multiple of 16 and at least 4 MiB");
+    return goq_launch_read_probe((hipStream_t)stream, buf, bytes, sink);
+}
+
+int goq_mfma_rate_probe(void *stream, int kind, int workgroups, int iters, float *sink, double *ops)
+{
+    if (!sink || !ops || misaligned(sink, 4)) return goq_set_error(GOQ_EINVAL, "goq_mfma_rate_probe: NULL or misaligned pointer");
+    if (kind < 0 || kind > 2) return goq_set_error(GOQ_EINVAL, "goq_mfma_rate_probe: kind = %d must be 0, 1 or 2", kind);
+    if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
+        return goq_set_error(GOQ_ESHAPE, "goq_mfma_rate_probe: workgroups or iters out of range");
+    return goq_launch_mfma_rate_probe((hipStream_t)stream, kind, workgroups, iters, sink, ops);
 }
 
 int goq_gemv_select(int kernel)
@@ -165,7 +189,65 @@ int goq_gemv_batch(void *stream, int bw, int act, int n, const goq_gemv_desc *de
         int rc = check_gemv_desc("goq_gemv_batch", bw, act, descs[i]);
         if (rc) return rc;
     }
-    return goq_launch_gemv((hipStream_t)stream, bw, act, n, descs);
+    return goq_launch_gemv((hipStream_t)stream, bw, act, n, descs, nullptr);
+}
+
+int goq_gemv_workspace_bytes(size_t *bytes)
+{
+    if (!bytes) return goq_set_error(GOQ_EINVAL, "goq_gemv_workspace_bytes: bytes is NULL");
+    *bytes = goq_gemv_workspace_size();
+    return GOQ_OK;
+}
+
+int goq_gemv_workspace_init(void *stream, void *workspace)
+{
+    if (!workspace || misaligned(workspace, 256))
+        return goq_set_error(GOQ_EINVAL, "goq_gemv_workspace_init: workspace must be a 256-byte aligned device pointer");
+    return goq_launch_gemv_workspace_init((hipStream_t)stream, workspace);
+}
+
+int goq_gemv_batch_ws(void *stream, int bw, int act, int n, const goq_gemv_desc *descs, void *workspace)
+{
+    if (!descs) return goq_set_error(GOQ_EINVAL, "goq_gemv_batch_ws: descs is NULL");
+    if (!workspace || misaligned(workspace, 256))
+        return goq_set_error(GOQ_EINVAL, "goq_gemv_batch_ws: workspace must be a 256-byte aligned device pointer");
+    if (n <= 0 || n > GOQ_MAX_BATCH)
+        return goq_set_error(GOQ_ESHAPE, "goq_gemv_batch_ws: n = %d must be in 1..%d", n, GOQ_MAX_BATCH);
+    for (int i = 0; i < n; ++i) {
+        int rc = check_gemv_desc("goq_gemv_batch_ws", bw, act, descs[i]);
+        if (rc) return rc;
+    }
+    return goq_launch_gemv((hipStream_t)stream, bw, act, n, descs, workspace);
+}
+
+int goq_gemv_stream_table_bytes(int n, size_t *bytes)
+{
+    if (!bytes) return goq_set_error(GOQ_EINVAL, "goq_gemv_stream_table_bytes: bytes is NULL");
+    if (n < 1 || n > GOQ_MAX_STREAM)
+        return goq_set_error(GOQ_ESHAPE, "goq_gemv_stream_table_bytes: n = %d must be in 1..%d", n, GOQ_MAX_STREAM);
+    *bytes = goq_gemv_stream_table_size(n);
+    return GOQ_OK;
+}
+
+int goq_gemv_stream_table(int bw, int act, int n, const goq_gemv_desc *descs, void *table)
+{
+    if (!descs || !table) return goq_set_error(GOQ_EINVAL, "goq_gemv_stream_table: NULL pointer");
+    if (misaligned(table, 8)) return goq_set_error(GOQ_EINVAL, "goq_gemv_stream_table: table must be 8-byte aligned");
+    if (n < 1 || n > GOQ_MAX_STREAM)
+        return goq_set_error(GOQ_ESHAPE, "goq_gemv_stream_table: n = %d must be in 1..%d", n, GOQ_MAX_STREAM);
+    for (int i = 0; i < n; ++i) {
+        int rc = check_gemv_desc("goq_gemv_stream_table", bw, act, descs[i]);
+        if (rc) return rc;
+    }
+    return goq_gemv_stream_build_table(bw, act, n, descs, table);
+}
+
+int goq_gemv_stream(void *stream, const void *table_host, const void *table_dev, void *workspace)
+{
+    if (!table_host || !table_dev || !workspace) return goq_set_error(GOQ_EINVAL, "goq_gemv_stream: NULL pointer");
+    if (misaligned(table_host, 8) || misaligned(table_dev, 16) || misaligned(workspace, 256))
+        return goq_set_error(GOQ_EINVAL, "goq_gemv_stream: table_dev must be 16-byte, workspace 256-byte aligned");
+    return goq_launch_gemv_stream((hipStream_t)stream, table_host, table_dev, workspace);
 }
 
 static int check_gemm_desc(const char *fn, int bw, int act, const goq_gemm_desc &d)

@@ -33,12 +33,22 @@
 // file instead, gemv_rows_kernel: one workgroup per 16 rows over the whole depth, no combine.)
 //
 // Where a piece boundary falls inside a row group, each wavefront publishes the partial sums of
-// its 64 rows to a per-library scratch area and the LAST wavefront to arrive (an atomic counter
-// per boundary and row block) adds the parts in workgroup order and stores y: no zero-fill
-// pass, no floating-point atomics, and the result does not depend on timing.
+// its 64 rows to a workspace and the LAST wavefront to arrive (an atomic counter per boundary
+// and row block) adds the parts in workgroup order and stores y: no zero-fill pass, no
+// floating-point atomics, and the result does not depend on timing.  The workspace is the
+// caller's (goq_gemv_batch_ws, goq_gemv_stream) or one of the library's static regions, one per
+// stream (goq_gemv, goq_gemv_batch).
+//
+// The same kernel body runs in two forms: with up to GOQ_MAX_BATCH problems in the kernel
+// arguments (goq_gemv_batch: the lowest start-up latency), and with a problem table in device
+// memory (goq_gemv_stream: thousands of problems -- e.g. every projection of every decoder block
+// of a model -- as ONE unit sequence, so that start-up and tail are paid once per stream).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <atomic>
+#include <mutex>
+#include <string.h>
+#include <stdio.h>
 #include <type_traits>
 #include "goq_layout.h"
 #include "goq_decode.h"
@@ -66,13 +76,16 @@ constexpr int XZ = 256;                  // zero bytes in front of the digit tab
 #define GOQ_CB 16
 #endif
 constexpr int CB = GOQ_CB;               // parts a combining wavefront requests at a time
-constexpr int REGIONS = 8;               // scratch regions handed out round-robin to launches
+constexpr int REGIONS = 8;               // static scratch regions: one per stream that launches
 
+// Workspace of one launch: the parts of the row groups cut by a piece boundary.
 struct Region {
     float partials[MAX_WG][2][NT];       // [workgroup][head | tail][row of the row group]
     unsigned counters[MAX_WG][WAVES];    // arrivals per boundary (first contributor) and row block
 };
-__device__ __attribute__((aligned(256))) Region g_scratch[REGIONS];
+// The library's own regions, for the entry points that take no workspace.  Host code never uses
+// this name as an address: region_of_stream() resolves the device address once per device.
+static __device__ __align__(256) Region scratch[REGIONS];
 
 struct GemvProblem {
     const uint32_t *packed;
@@ -86,6 +99,7 @@ struct GemvProblem {
     int rgroups;     // row groups
     int begin;       // first unit of this problem in the linear unit sequence
     int bb;          // first 16-row block of this problem in the grid of the row-owner kernel
+    int pad;
 };
 
 struct GemvArgs {
@@ -94,6 +108,44 @@ struct GemvArgs {
     int pq, pr;      // total / workgroups, total % workgroups
     Region *scratch;
     GemvProblem p[GOQ_MAX_BATCH];
+};
+
+// Problem table of goq_gemv_stream (built on the host by goq_gemv_stream_table, copied to the
+// device by the caller): this header, then the n problems.
+constexpr uint32_t TABLE_MAGIC = 0x51544247u;
+struct GemvTable {
+    uint32_t magic;
+    int bw, act;
+    int n;
+    int total;       // units of the whole stream
+    int nwg;         // workgroups (= pieces) of the launch
+    int pq, pr;      // total / nwg, total % nwg
+    int pad[8];
+    int first[MAX_WG];   // the problem that holds the first unit of each piece
+};
+
+// Where the problems of a launch live: in the kernel arguments (up to GOQ_MAX_BATCH) or in a
+// table in device memory.
+template <bool TABLE>
+struct Problems;
+template <>
+struct Problems<false> {
+    const GemvArgs &a;
+    __device__ __forceinline__ const GemvProblem &operator[](int i) const { return a.p[i]; }
+    __device__ __forceinline__ int n() const { return a.n; }
+};
+template <>
+struct Problems<true> {
+    const GemvProblem *__restrict__ t;
+    int cnt;
+    __device__ __forceinline__ const GemvProblem &operator[](int i) const { return t[i]; }
+    __device__ __forceinline__ int n() const { return cnt; }
+};
+
+// The piece decomposition of a launch and its workspace.
+struct Pieces {
+    int pq, pr;
+    Region *scratch;
 };
 
 // Exchange table entry of variant v = pattern | signs << 2 (Theorem 1) for decoded BYTES:
@@ -260,87 +312,96 @@ struct Cursor {
     int pi, rg, g;
 };
 
-__device__ __forceinline__ Cursor locate(const GemvArgs &a, int idx)
-{
-    Cursor c;
-    int pi = 0;
-    while (pi + 1 < a.n && idx >= a.p[pi + 1].begin) ++pi;
-    const int local = idx - a.p[pi].begin;
-    c.pi = pi;
-    c.rg = local / a.p[pi].gn;
-    c.g = local % a.p[pi].gn;
-    return c;
-}
-
-// The few fields of a problem the streaming loop needs, read from the kernel arguments once per
-// problem and kept in scalar registers.
+// The few fields of a problem the streaming loop needs, read once per problem and kept in scalar
+// registers.  end: first unit of the next problem.
 struct Stream {
     const uint32_t *packed;
-    int gn, rbn, rgroups;
+    int gn, rbn, rgroups, end;
 };
 
-__device__ __forceinline__ Stream stream_of(const GemvArgs &a, int pi)
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <bool TABLE>
+__device__ __forceinline__ Stream stream_of(const Problems<TABLE> &pb, int pi)
 {
     Stream s;
-    const uint64_t pk = (uint64_t)a.p[pi].packed;
-    s.packed = (const uint32_t *)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(pk >> 32)) << 32) |
-                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)pk));
-    s.gn = __builtin_amdgcn_readfirstlane(a.p[pi].gn);
-    s.rbn = __builtin_amdgcn_readfirstlane(a.p[pi].rbn);
-    s.rgroups = __builtin_amdgcn_readfirstlane(a.p[pi].rgroups);
+    const GemvProblem &P = pb[pi];
+    const uint64_t pk = (uint64_t)P.packed;
+    s.packed = (const uint32_t *)(((uint64_t)(uint32_t)uniform((int)(pk >> 32)) << 32) | (uint32_t)uniform((int)pk));
+    s.gn = uniform(P.gn);
+    s.rbn = uniform(P.rbn);
+    s.rgroups = uniform(P.rgroups);
+    s.end = uniform(P.begin + P.rgroups * P.gn);
     return s;
 }
 
 // Digits of the units [u0, u0 + ns) of the sequence, unit s into table slot s.  Thread
-// (slot = tid / 16, run = tid % 16); ns <= SW = NT / 32.
-template <int ACT>
-__device__ __forceinline__ void stage_window(const GemvArgs &a, int u0, int ns, unsigned char *xt,
-                                             unsigned char *st, int tid)
+// (slot = tid / 16, run = tid % 16); ns <= SW = NT / 32.  u0 lies in problem pi0, whose units end
+// at end0; units past it belong to the following problems.
+template <int ACT, bool TABLE>
+__device__ __forceinline__ void stage_window(const Problems<TABLE> &pb, int pi0, int end0, int u0, int ns,
+                                             unsigned char *xt, unsigned char *st, int tid)
 {
     if (tid < ns * 16) {
         const int slot = tid >> 4;
-        const Cursor c = locate(a, u0 + slot);
-        stage_run<ACT>(xt + slot * XG, st + slot * 4, a.p[c.pi].x, c.g, tid & 15);
+        const int u = u0 + slot;
+        int pi = pi0;
+        if (u >= end0) {
+            ++pi;
+            while (pi + 1 < pb.n() && u >= pb[pi + 1].begin) ++pi;
+        }
+        const GemvProblem &P = pb[pi];
+        stage_run<ACT>(xt + slot * XG, st + slot * 4, P.x, (u - P.begin) % P.gn, tid & 15);
     }
 }
 
-// ---- one 16-row slice of a macro-block (H2..H4) ---------------------------------------------
+// ---- one 16-row slice of a macro-block (decode, exchange, the two slab dot products) ---------
 // quad: the lane's quad (chunk q, row c of the slice); md (bw = 4): the metadata dword of that
-// chunk and row; vt: LDS address of this lane's copy of the exchange table; A, sa: the macro-block's digits (this lane's A row and k-group) and their
-// block scale.  P1, P2: this lane group's two digit sums of row c against b1 and b2.
+// chunk and row; vt: LDS address of this lane's copy of the exchange table; A, sa: the
+// macro-block's digits (this lane's A row and k-group) and their block scale.  D1, D2: the
+// matrix instruction's results against b1 and b2; this lane group's two digit sums of row c are
+// elements 0 and 1.
 template <int BW>
 __device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t md, uint32_t vt,
-                                               const v8i &A, int sa, float &P1, float &P2)
+                                               const v8i &A, int sa, v4f &D1, v4f &D2)
 {
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
     const uint32_t dw[4] = {quad.x, quad.y, quad.z, quad.w};
-    v8i B1, B2;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t w = dw[k];
-        uint32_t lo, hi;
-        goq_decode_bytes<BW, 0>(w, lo, hi);                          // H2: code -> E5M2 byte
+    // LA exchange-table entries are requested ahead, so that the look-ups are in flight while the
+    // primary codes are decoded (bw = 4 has fewer registers to spare)
+    constexpr int LA = (BW == 3) ? 4 : 2;
+    u32x4 ev[4];
+    auto request = [&](int k) {
         uint32_t eo;                       // LDS address of the entry: vt + 64 * (pattern | signs << 2)
         if constexpr (BW == 3) {
             // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
             // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
-            eo = __builtin_amdgcn_udot4(w & 0x00C0C0C0u, 0x00100401u, vt, false);
+            eo = __builtin_amdgcn_udot4(dw[k] & 0x00C0C0C0u, 0x00100401u, vt, false);
         } else {
             eo = vt + (((md >> (6 * k)) & 63u) << 6);
         }
-        const u32x4 ev = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
-        const uint4 e = make_uint4(ev.x, ev.y, ev.z, ev.w);
+        ev[k] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
+    };
+#pragma unroll
+    for (int k = 0; k < LA; ++k) request(k);
+    v8i B1, B2;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t lo, hi;
+        goq_decode_bytes<BW, 0>(dw[k], lo, hi);                      // code -> E5M2 byte
         B1[2 * k] = (int)lo;
         B1[2 * k + 1] = (int)hi;
-        B2[2 * k] = (int)(goq_perm(hi, lo, e.x) ^ e.z);               // H4: exchange + sign XOR
-        B2[2 * k + 1] = (int)(goq_perm(hi, lo, e.y) ^ e.w);
     }
-    // H3 / H4 accumulate: E5M2 x E5M2, fp32 accumulation; block scale sa on the activation
-    // side, 2^0 on the weight side
-    const v4f D1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B1, zero, 1, 1, 0, sa, 0, 127);
-    const v4f D2 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B2, zero, 1, 1, 0, sa, 0, 127);
-    P1 = D1[0] + D1[1];
-    P2 = D2[0] + D2[1];
+    // E5M2 x E5M2, fp32 accumulation; block scale sa on the activation side, 2^0 on the weight side
+    D1 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B1, zero, 1, 1, 0, sa, 0, 127);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t lo = (uint32_t)B1[2 * k], hi = (uint32_t)B1[2 * k + 1];
+        B2[2 * k] = (int)(goq_perm(hi, lo, ev[k].x) ^ ev[k].z);       // Theorem 1 exchange + sign XOR
+        B2[2 * k + 1] = (int)(goq_perm(hi, lo, ev[k].y) ^ ev[k].w);
+        if (k + LA < 4) request(k + LA);
+    }
+    D2 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B2, zero, 1, 1, 0, sa, 0, 127);
 }
 
 // A row's coefficient word is spread over what its four lanes (c, 0..3) load, one byte each: two
@@ -362,15 +423,16 @@ __device__ __forceinline__ uint32_t coefficient_byte(const uint4 &quad, uint32_t
 template <int BW>
 __device__ __forceinline__ int coefficient_byte_position(int q) { return BW == 3 ? 3 - q : q; }
 
-// H5: coefficient rescale, once per slab, outside the dot-product loop
-__device__ __forceinline__ float rescale(uint32_t cword, float P1, float P2, float acc)
+// Coefficient rescale (Eq. 4), once per slab, outside the dot-product loop: the two digit sums
+// this lane group received for each basis, times the slab's coefficient pair.
+__device__ __forceinline__ float rescale(uint32_t cword, const v4f &D1, const v4f &D2, float acc)
 {
     const float c1 = __half2float(__ushort_as_half((unsigned short)(cword & 0xffffu)));
     const float c2 = __half2float(__ushort_as_half((unsigned short)(cword >> 16)));
-    return fmaf(c2, P2, fmaf(c1, P1, acc));
+    return fmaf(c2, D2[0] + D2[1], fmaf(c1, D1[0] + D1[1], acc));
 }
 
-// ---- one unit of one wavefront: 64 rows x one macro-block (H2..H5) --------------------------
+// ---- one unit of one wavefront: 64 rows x one macro-block --------------------------------------
 // buf: the lane's quads; cwx: this wavefront's 256-byte exchange area for coefficient bytes;
 // acc[j]: running sum of row 16 j + c over the digits this lane receives.
 template <int BW>
@@ -387,37 +449,56 @@ __device__ __forceinline__ void compute_unit(const UnitBuf<BW> &buf, uint32_t vt
     for (int j = 0; j < 4; ++j)
         cwx[j * 64 + c * 4 + cpos] = (unsigned char)coefficient_byte<BW>(buf.q[j], buf.md[BW == 4 ? j : 0]);
     asm volatile("" ::: "memory");
+    // bw = 3: the rescale of slice j is issued after the matrix instructions of slice j + 1, whose
+    // decode covers the latency of slice j's results (bw = 4 has no registers to spare for that).
+    constexpr bool DEFER = (BW == 3);
+    v4f D1[2], D2[2];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        float P1, P2;
-        slice_products<BW>(buf.q[j], buf.md[BW == 4 ? j : 0], vt, A, sa, P1, P2);
-        const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + j * 64 + c * 4);
-        acc[j] = rescale(cword, P1, P2, acc[j]);
+        slice_products<BW>(buf.q[j], buf.md[BW == 4 ? j : 0], vt, A, sa, D1[j & 1], D2[j & 1]);
+        const int jr = DEFER ? j - 1 : j;
+        if (jr >= 0) {
+            const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + jr * 64 + c * 4);
+            acc[jr] = rescale(cword, D1[jr & 1], D2[jr & 1], acc[jr]);
+        }
+    }
+    if constexpr (DEFER) {
+        const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + 3 * 64 + c * 4);
+        acc[3] = rescale(cword, D1[1], D2[1], acc[3]);
     }
 }
 
 // The unit sequence is cut into nwg pieces: the first `pr` workgroups take pq + 1 units, the others
 // pq (pq = total / nwg and pr = total % nwg come from the host).
 // first unit of workgroup b's piece
-__device__ __forceinline__ int piece_begin(const GemvArgs &a, int b)
+__device__ __forceinline__ int piece_begin(const Pieces &pc, int b)
 {
-    return b * a.pq + min(b, a.pr);
+    return b * pc.pq + min(b, pc.pr);
 }
 
 // the workgroup whose piece holds unit u
-__device__ __forceinline__ int piece_of(const GemvArgs &a, int u)
+__device__ __forceinline__ int piece_of(const Pieces &pc, int u)
 {
-    const int big = a.pr * (a.pq + 1);                      // units held by the larger pieces
-    return u < big ? u / (a.pq + 1) : a.pr + (u - big) / a.pq;
+    const int big = pc.pr * (pc.pq + 1);                    // units held by the larger pieces
+    return u < big ? u / (pc.pq + 1) : pc.pr + (u - big) / pc.pq;
 }
 
-// H6 for the 64 rows of one wavefront: acc[j] of lanes (c, 0) and (c, 1) add up to the sum of row
-// 16 j + c over the units [max(u0, i0), min(u1, i1)) of its row group.
+// Reduce + store for the 64 rows of one wavefront: acc[j] of lanes (c, 0..3) add up to the sum of
+// row 16 j + c over the units [max(u0, i0), min(u1, i1)) of its row group.
+//
+// Split row groups.  Every contributor writes its 64 parts with agent-scope atomic stores (they go
+// through to memory, past the L2 of its XCD), waits until they have been acknowledged
+// (s_waitcnt vmcnt(0): the hardware form of "these stores happen before what follows"), and then
+// counts itself in with an agent-scope atomic add on the boundary's counter.  The contributor whose
+// add returns the last count reads all parts with agent-scope atomic loads (which do not hit in a
+// stale L2 line) -- every one of them was acknowledged before its writer's add, and the adds are
+// totally ordered at the counter, so the reader's loads come after all the stores.  This is a
+// release (stores, wait, add) / acquire (add, loads) pair built from per-access scopes instead of
+// fences: an agent-scope release FENCE would write back the whole L2 for 256 bytes of parts.
 template <int ACT>
-__device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, float (&acc)[4], int i0, int i1,
-                                      int wave, int lane)
+__device__ __forceinline__ void flush(const GemvProblem &P, const Pieces &pc, const Cursor &cur, float (&acc)[4],
+                                      int i0, int i1, int wave, int lane)
 {
-    const GemvProblem &P = a.p[cur.pi];
     const int u0 = P.begin + cur.rg * P.gn, u1 = u0 + P.gn;
     // lane l takes over row l of the row block: the sum of row 16 j + c is spread over the four
     // lanes c, c + 16, c + 32, c + 48 (two digits each)
@@ -442,23 +523,20 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
         store(mine);
         return;
     }
-    // partial: publish, count arrivals, the last arrival adds the parts in workgroup order.
-    // The parts are written and read with device-scope accesses and the counter is a device-scope
-    // atomic, so no cache write-back / invalidate fence is needed: a wavefront waits until its own
-    // part has been acknowledged, then counts itself in.  Of the contributors bf..bl only the
-    // first can hold the row group as the tail of its piece (slot 1); for the others it is the head.
-    Region *S = a.scratch;
+    // Of the contributors bf..bl only the first can hold the row group as the tail of its piece
+    // (slot 1); for the others it is the head.
+    Region *S = pc.scratch;
     const int b = blockIdx.x;
     __hip_atomic_store(&S->partials[b][i0 > u0 ? 0 : 1][rl], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int bf = piece_of(a, u0), bl = piece_of(a, u1 - 1);
+    const int bf = piece_of(pc, u0), bl = piece_of(pc, u1 - 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     unsigned old = 0;
     if (lane == 0) {
         old = __hip_atomic_fetch_add(&S->counters[bf][wave], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old == (unsigned)(bl - bf))
+        if (old == (unsigned)(bl - bf))                    // back to zero for the next launch
             __hip_atomic_store(&S->counters[bf][wave], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    old = (unsigned)__builtin_amdgcn_readfirstlane((int)old);
+    old = (unsigned)uniform((int)old);
     if (old == (unsigned)(bl - bf)) {
         float s = __hip_atomic_load(&S->partials[bf][1][rl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int w = bf + 1; w <= bl; w += CB) {           // CB independent loads at a time
@@ -474,53 +552,22 @@ __device__ __forceinline__ void flush(const GemvArgs &a, const Cursor &cur, floa
     }
 }
 
-// The leading scalar arguments repeat what the first instructions of a workgroup need -- the piece
-// sizes and the first unit of every problem -- as separate kernel arguments, so that they can be
-// preloaded into scalar registers at wavefront launch (-amdgpu-kernarg-preload-count): finding
-// the workgroup's first unit then costs no memory round trip, and its weights are requested one
-// round trip (the problem's fields) after the wavefront starts.
-template <int BW, int ACT>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ_WPE)))
-void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, int bg6, int bg7, GemvArgs a)
+// ---- the streaming loop of one workgroup over its piece [i0, i1) ------------------------------
+// cur: the position of unit i0.  LDS: xtab = zeros (the A rows without a digit), then the digit
+// table of the resident units; stab = its block scales; vtab = exchange table, entry v at
+// 64 v + 16 r, four copies r (a lane uses copy lane % 4); cwx = coefficient-byte exchange.
+template <int BW, int ACT, bool TABLE>
+__device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pieces &pc, int i0, int i1, Cursor cur,
+                                             unsigned char *xtab, unsigned char *stab, unsigned char *vtab,
+                                             unsigned char *cwx)
 {
-    // zeros (the A rows without a digit), then the digit table of the resident units and its block scales
-    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];
-    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];
-    // exchange table: entry v at 64 v + 16 r, four copies r (a lane uses copy lane % 4)
-    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];
-    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256];
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    // this workgroup's piece [i0, i1) of the unit sequence
-    const int bid = blockIdx.x;
-    const int i0 = __builtin_amdgcn_readfirstlane(bid * pq + min(bid, pr));
-    const int i1 = __builtin_amdgcn_readfirstlane((bid + 1) * pq + min(bid + 1, pr));
-    if (i0 >= i1) return;
-
-    // the problem that holds unit i0, by compares with the (preloaded) first units: unused
-    // problems start at INT_MAX
-    Cursor cur;
-    {
-        const int bg[GOQ_MAX_BATCH] = {0, bg1, bg2, bg3, bg4, bg5, bg6, bg7};
-        int pi = 0, b0 = 0;
-#pragma unroll
-        for (int i = 1; i < GOQ_MAX_BATCH; ++i) {
-            const bool ge = i0 >= bg[i];
-            pi += ge ? 1 : 0;
-            b0 = ge ? bg[i] : b0;
-        }
-        const int gn = a.p[pi].gn;
-        cur.pi = __builtin_amdgcn_readfirstlane(pi);
-        cur.rg = __builtin_amdgcn_readfirstlane((i0 - b0) / gn);
-        cur.g = __builtin_amdgcn_readfirstlane((i0 - b0) % gn);
-    }
+    const int wave = uniform(tid >> 6);
 
     // the first unit's weights are requested before anything else
     UnitBuf<BW> bufA, bufB;
-    Stream S = stream_of(a, cur.pi);
+    Stream S = stream_of(pb, cur.pi);
     load_unit<BW>(S.packed, S.gn, min(cur.rg * WAVES + wave, S.rbn - 1), cur.g, lane, bufA);
 
     for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
@@ -548,14 +595,14 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
         const int slot = (idx - i0) % SW;
         if (slot == 0) {
             if (idx != i0) __syncthreads();                    // everyone is done with the old window
-            stage_window<ACT>(a, idx, min(SW, i1 - idx), xtab + XZ, stab, tid);
+            stage_window<ACT, TABLE>(pb, cur.pi, S.end, idx, min(SW, i1 - idx), xtab + XZ, stab, tid);
             __syncthreads();
         }
         Cursor nxt = cur;
         if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
         Stream Sn = S;
         if constexpr (MORE) {
-            if (nxt.pi != cur.pi) Sn = stream_of(a, nxt.pi);
+            if (nxt.pi != cur.pi) Sn = stream_of(pb, nxt.pi);
             load_unit<BW>(Sn.packed, Sn.gn, min(nxt.rg * WAVES + wave, Sn.rbn - 1), nxt.g, lane, bnxt);
         }
         const int R = cur.rg * WAVES + wave;
@@ -567,7 +614,7 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
             compute_unit<BW>(bcur, vt_lane, A, sa, cwx + wave * 256, lane, acc);
         }
         if (!MORE || nxt.rg != cur.rg || nxt.pi != cur.pi) {
-            if (live) flush<ACT>(a, cur, acc, i0, i1, wave, lane);
+            if (live) flush<ACT>(pb[cur.pi], pc, cur, acc, i0, i1, wave, lane);
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[j] = 0.f;
         }
@@ -582,6 +629,84 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
         else { step(bufB, bufA, std::false_type{}); break; }
     }
 }
+
+#define GOQ_GEMV_LDS                                                                        \
+    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];               \
+    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];                     \
+    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];                    \
+    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256]
+
+// Problems in the kernel arguments.  The leading scalar arguments repeat what the first
+// instructions of a workgroup need -- the piece sizes and the first unit of every problem -- as
+// separate kernel arguments, so that they can be preloaded into scalar registers at wavefront
+// launch (-amdgpu-kernarg-preload-count): finding the workgroup's first unit then costs no memory
+// round trip, and its weights are requested one round trip (the problem's fields) after the
+// wavefront starts.
+template <int BW, int ACT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ_WPE)))
+void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, int bg6, int bg7, GemvArgs a)
+{
+    GOQ_GEMV_LDS;
+    // this workgroup's piece [i0, i1) of the unit sequence
+    const int bid = blockIdx.x;
+    const int i0 = uniform(bid * pq + min(bid, pr));
+    const int i1 = uniform((bid + 1) * pq + min(bid + 1, pr));
+    if (i0 >= i1) return;
+
+    // the problem that holds unit i0, by compares with the (preloaded) first units: unused
+    // problems start at INT_MAX
+    Cursor cur;
+    {
+        const int bg[GOQ_MAX_BATCH] = {0, bg1, bg2, bg3, bg4, bg5, bg6, bg7};
+        int pi = 0, b0 = 0;
+#pragma unroll
+        for (int i = 1; i < GOQ_MAX_BATCH; ++i) {
+            const bool ge = i0 >= bg[i];
+            pi += ge ? 1 : 0;
+            b0 = ge ? bg[i] : b0;
+        }
+        const int gn = a.p[pi].gn;
+        cur.pi = uniform(pi);
+        cur.rg = uniform((i0 - b0) / gn);
+        cur.g = uniform((i0 - b0) % gn);
+    }
+    const Problems<false> pb{a};
+    const Pieces pc{pq, pr, a.scratch};
+    stream_piece<BW, ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
+}
+
+// Problems in a table in device memory (goq_gemv_stream).
+template <int BW, int ACT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(GOQ_WPE, GOQ_WPE)))
+void gemv_stream_kernel(const GemvTable *__restrict__ T, Region *ws)
+{
+    GOQ_GEMV_LDS;
+    const int bid = blockIdx.x;
+    const int pq = uniform(T->pq), pr = uniform(T->pr);
+    const int i0 = uniform(bid * pq + min(bid, pr));
+    const int i1 = uniform((bid + 1) * pq + min(bid + 1, pr));
+    if (i0 >= i1) return;
+    const Problems<true> pb{reinterpret_cast<const GemvProblem *>(T + 1), uniform(T->n)};
+    Cursor cur;
+    cur.pi = uniform(T->first[bid]);
+    {
+        const GemvProblem &P = pb[cur.pi];
+        const int local = i0 - P.begin, gn = P.gn;
+        cur.rg = uniform(local / gn);
+        cur.g = uniform(local % gn);
+    }
+    const Pieces pc{pq, pr, ws};
+    stream_piece<BW, ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
+}
+
+// Zero-fill of a caller-owned workspace (a kernel, not a memset node, so that a caller may
+// capture it).
+__global__ __launch_bounds__(256) void workspace_init_kernel(Region *ws)
+{
+    unsigned *c = &ws->counters[0][0];
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < MAX_WG * WAVES; i += gridDim.x * blockDim.x) c[i] = 0u;
+}
+
 
 // ---- small layers: one workgroup per 16 output rows ------------------------------------------
 // When a launch has few units per workgroup of the kernel above, each row group is cut among up
@@ -675,9 +800,9 @@ void gemv_rows_kernel(GemvArgs a)
                 const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
                 const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
                 const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * digit;
-                float P1, P2;
-                slice_products<BW>(cur[i].q, cur[i].md, vt_lane, A, sa, P1, P2);
-                acc = rescale(*reinterpret_cast<const uint32_t *>(cw + i * 64 + c * 4), P1, P2, acc);
+                v4f D1, D2;
+                slice_products<BW>(cur[i].q, cur[i].md, vt_lane, A, sa, D1, D2);
+                acc = rescale(*reinterpret_cast<const uint32_t *>(cw + i * 64 + c * 4), D1, D2, acc);
             }
         }
 #pragma unroll
@@ -715,28 +840,111 @@ int launch(hipStream_t st, const GemvArgs &a, int nwg)
     return goq_check_launch("goq_gemv");
 }
 
-// device address of the scratch regions, looked up once per device
-Region *scratch_base()
+template <int BW, int ACT>
+int launch_stream(hipStream_t st, const GemvTable *dev, Region *ws, int nwg)
 {
-    constexpr int MAXDEV = 64;
-    static std::atomic<Region *> base[MAXDEV];
+    hipLaunchKernelGGL((gemv_stream_kernel<BW, ACT>), dim3(nwg), dim3(NT), 0, st, dev, ws);
+    return goq_check_launch("goq_gemv_stream");
+}
+
+// ---- the library's static regions ---------------------------------------------------------------
+// Launches on one stream run one after the other, so a region per stream is never shared by two
+// launches in flight.  Per device: the device address of `scratch` (looked up once, with that
+// device current) and which stream owns which region.
+constexpr int MAXDEV = 64;
+struct DeviceRegions {
+    Region *base = nullptr;
+    hipStream_t owner[REGIONS] = {};
+    bool used[REGIONS] = {};
+    unsigned long long stamp[REGIONS] = {};
+};
+DeviceRegions g_regions[MAXDEV];
+unsigned long long g_clock = 0;
+std::mutex g_regions_mutex;
+
+// Region of stream st on the current device, or nullptr with *rc set.
+Region *region_of_stream(hipStream_t st, int *rc)
+{
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAXDEV) return nullptr;
-    Region *p = base[dev].load(std::memory_order_acquire);
-    if (!p) {
-        void *sym = nullptr;
-        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_scratch)) != hipSuccess || !sym) return nullptr;
-        p = reinterpret_cast<Region *>(sym);
-        base[dev].store(p, std::memory_order_release);
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAXDEV) {
+        *rc = goq_set_error(GOQ_EHIP, "goq_gemv: cannot tell the current device");
+        return nullptr;
     }
-    return p;
+    std::lock_guard<std::mutex> lock(g_regions_mutex);
+    DeviceRegions &D = g_regions[dev];
+    if (!D.base) {
+        void *sym = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !sym) {
+            *rc = goq_set_error(GOQ_EHIP, "goq_gemv: cannot resolve the scratch area on device %d: %s", dev,
+                                hipGetErrorString(e));
+            return nullptr;
+        }
+        D.base = reinterpret_cast<Region *>(sym);
+    }
+    ++g_clock;
+    int free_slot = -1;
+    for (int i = 0; i < REGIONS; ++i) {
+        if (D.used[i] && D.owner[i] == st) { D.stamp[i] = g_clock; return D.base + i; }
+        if (!D.used[i] && free_slot < 0) free_slot = i;
+    }
+    if (free_slot < 0) {
+        // All regions have an owner: take over the least recently used one, after waiting on the
+        // host until its stream has drained (the only call of this library that may block; a
+        // stream that no longer exists counts as drained).  Not possible while either stream is
+        // being captured.
+        int lru = 0;
+        for (int i = 1; i < REGIONS; ++i)
+            if (D.stamp[i] < D.stamp[lru]) lru = i;
+        hipStreamCaptureStatus mine = hipStreamCaptureStatusNone, theirs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &mine) != hipSuccess) (void)hipGetLastError();
+        const bool gone = hipStreamIsCapturing(D.owner[lru], &theirs) != hipSuccess;
+        if (gone) (void)hipGetLastError();
+        if (mine != hipStreamCaptureStatusNone || (!gone && theirs != hipStreamCaptureStatusNone)) {
+            *rc = goq_set_error(GOQ_EUNSUPPORTED,
+                                "goq_gemv: all %d scratch regions of device %d belong to other streams and one of the "
+                                "streams involved is being captured; use goq_gemv_batch_ws with a workspace of your own",
+                                REGIONS, dev);
+            return nullptr;
+        }
+        if (!gone && hipStreamSynchronize(D.owner[lru]) != hipSuccess) (void)hipGetLastError();
+        free_slot = lru;
+    }
+    D.used[free_slot] = true;
+    D.owner[free_slot] = st;
+    D.stamp[free_slot] = g_clock;
+    return D.base + free_slot;
 }
 
 std::atomic<int> g_kernel{GOQ_GEMV_AUTO};
 
+void fill_problem(GemvProblem &P, const goq_gemv_desc &d)
+{
+    P.packed = (const uint32_t *)d.packed;
+    P.x = d.x;
+    P.sx = d.sx;
+    P.y = d.y;
+    P.out = (int)d.out;
+    P.gn = (int)(d.in / GOQ_N);
+    P.ytype = d.ytype;
+    P.rbn = (int)goq_row_blocks(d.out);
+    P.rgroups = (P.rbn + WAVES - 1) / WAVES;
+    P.begin = 0;
+    P.bb = 0;
+    P.pad = 0;
+}
+
 }  // namespace
 
 void goq_gemv_set_kernel(int kernel) { g_kernel.store(kernel, std::memory_order_relaxed); }
+
+size_t goq_gemv_workspace_size() { return sizeof(Region); }
+
+int goq_launch_gemv_workspace_init(hipStream_t st, void *workspace)
+{
+    hipLaunchKernelGGL(workspace_init_kernel, dim3(16), dim3(256), 0, st, reinterpret_cast<Region *>(workspace));
+    return goq_check_launch("goq_gemv_workspace_init");
+}
 
 // Which kernel a launch of these problems takes under the current selection, and with how many
 // workgroups (host logic only).
@@ -759,54 +967,42 @@ int goq_gemv_plan_launch(int n, const goq_gemv_desc *descs, int *kernel, int *wo
     return GOQ_OK;
 }
 
-int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs)
+// workspace: the caller's, or NULL for the library's region of this stream
+int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc *descs, void *workspace)
 {
     int kernel = 0, workgroups = 0;
-    const int rc = goq_gemv_plan_launch(n, descs, &kernel, &workgroups);
+    int rc = goq_gemv_plan_launch(n, descs, &kernel, &workgroups);
     if (rc) return rc;
     GemvArgs a;
     a.n = n;
-    int64_t total = 0;
+    a.scratch = nullptr;
+    int64_t total = 0, blocks = 0;
     for (int i = 0; i < n; ++i) {
         GemvProblem &P = a.p[i];
-        P.packed = (const uint32_t *)descs[i].packed;
-        P.x = descs[i].x;
-        P.sx = descs[i].sx;
-        P.y = descs[i].y;
-        P.out = (int)descs[i].out;
-        P.gn = (int)(descs[i].in / GOQ_N);
-        P.ytype = descs[i].ytype;
-        P.rbn = (int)goq_row_blocks(descs[i].out);
-        P.rgroups = (P.rbn + WAVES - 1) / WAVES;
+        fill_problem(P, descs[i]);
         P.begin = (int)total;
         total += (int64_t)P.rgroups * P.gn;
+        P.bb = (int)blocks;
+        blocks += (descs[i].out + 15) / 16;
     }
-    for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].begin = 0x7fffffff; }
+    for (int i = n; i < GOQ_MAX_BATCH; ++i) { a.p[i] = a.p[0]; a.p[i].begin = 0x7fffffff; a.p[i].bb = 0x7fffffff; }
     a.total = (int)total;
-    // Small launches go to the row-owner kernel: one workgroup per 16 output rows.
-    {
-        int64_t blocks = 0;
-        for (int i = 0; i < n; ++i) {
-            a.p[i].bb = (int)blocks;
-            blocks += (descs[i].out + 15) / 16;
-        }
-        for (int i = n; i < GOQ_MAX_BATCH; ++i) a.p[i].bb = 0x7fffffff;
-        if (kernel == GOQ_GEMV_ROWS) {
-            const int nb = workgroups;
-            if (bw == 3 && act == GOQ_A16) return launch_rows<3, 0>(st, a, nb);
-            if (bw == 3 && act == GOQ_A8) return launch_rows<3, 1>(st, a, nb);
-            if (bw == 4 && act == GOQ_A8) return launch_rows<4, 1>(st, a, nb);
-            if (bw == 3 && act == GOQ_A4) return launch_rows<3, 2>(st, a, nb);
-            if (bw == 4 && act == GOQ_A4) return launch_rows<4, 2>(st, a, nb);
-            return launch_rows<4, 0>(st, a, nb);
-        }
+    a.pq = a.pr = 0;
+    // Small launches go to the row-owner kernel: one workgroup per 16 output rows, no workspace.
+    if (kernel == GOQ_GEMV_ROWS) {
+        const int nb = workgroups;
+        if (bw == 3 && act == GOQ_A16) return launch_rows<3, 0>(st, a, nb);
+        if (bw == 3 && act == GOQ_A8) return launch_rows<3, 1>(st, a, nb);
+        if (bw == 4 && act == GOQ_A8) return launch_rows<4, 1>(st, a, nb);
+        if (bw == 3 && act == GOQ_A4) return launch_rows<3, 2>(st, a, nb);
+        if (bw == 4 && act == GOQ_A4) return launch_rows<4, 2>(st, a, nb);
+        return launch_rows<4, 0>(st, a, nb);
     }
-    // Scratch for row groups cut by a piece boundary.  Launches take the regions round-robin, so
-    // up to REGIONS launches may be in flight (on different streams) without sharing one.
-    static std::atomic<unsigned> ticket{0};
-    Region *base = scratch_base();
-    if (!base) return goq_set_error(GOQ_EHIP, "goq_gemv: cannot resolve the scratch area on this device");
-    a.scratch = base + ticket.fetch_add(1, std::memory_order_relaxed) % REGIONS;
+    a.scratch = reinterpret_cast<Region *>(workspace);
+    if (!a.scratch) {
+        a.scratch = region_of_stream(st, &rc);
+        if (!a.scratch) return rc;
+    }
     // two 512-thread workgroups per CU (4 wavefronts per SIMD)
     const int nwg = workgroups;
     a.pq = a.total / nwg;
@@ -817,4 +1013,53 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     if (bw == 3 && act == GOQ_A4) return launch<3, 2>(st, a, nwg);
     if (bw == 4 && act == GOQ_A4) return launch<4, 2>(st, a, nwg);
     return launch<4, 0>(st, a, nwg);
+}
+
+// ---- goq_gemv_stream: the problem table ---------------------------------------------------------
+size_t goq_gemv_stream_table_size(int n) { return sizeof(GemvTable) + (size_t)n * sizeof(GemvProblem); }
+
+int goq_gemv_stream_build_table(int bw, int act, int n, const goq_gemv_desc *descs, void *table)
+{
+    GemvTable *T = reinterpret_cast<GemvTable *>(table);
+    GemvProblem *P = reinterpret_cast<GemvProblem *>(T + 1);
+    memset(T, 0, sizeof(GemvTable));
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        fill_problem(P[i], descs[i]);
+        P[i].begin = (int)total;
+        total += (int64_t)P[i].rgroups * P[i].gn;
+        if (total > 0x3fffffff) return goq_set_error(GOQ_ESHAPE, "goq_gemv_stream_table: too much work for one stream");
+    }
+    T->magic = TABLE_MAGIC;
+    T->bw = bw;
+    T->act = act;
+    T->n = n;
+    T->total = (int)total;
+    T->nwg = (int)(total < MAX_WG ? total : MAX_WG);
+    T->pq = T->total / T->nwg;
+    T->pr = T->total % T->nwg;
+    int pi = 0;
+    for (int b = 0; b < MAX_WG; ++b) {
+        const int64_t i0 = (int64_t)b * T->pq + (b < T->pr ? b : T->pr);
+        if (b >= T->nwg) { T->first[b] = 0; continue; }
+        while (pi + 1 < n && i0 >= P[pi + 1].begin) ++pi;
+        T->first[b] = pi;
+    }
+    return GOQ_OK;
+}
+
+int goq_launch_gemv_stream(hipStream_t st, const void *table_host, const void *table_dev, void *workspace)
+{
+    const GemvTable *T = reinterpret_cast<const GemvTable *>(table_host);
+    if (T->magic != TABLE_MAGIC || T->n < 1 || T->nwg < 1 || T->nwg > MAX_WG)
+        return goq_set_error(GOQ_EINVAL, "goq_gemv_stream: table_host was not written by goq_gemv_stream_table");
+    const GemvTable *dev = reinterpret_cast<const GemvTable *>(table_dev);
+    Region *ws = reinterpret_cast<Region *>(workspace);
+    const int bw = T->bw, act = T->act, nwg = T->nwg;
+    if (bw == 3 && act == GOQ_A16) return launch_stream<3, 0>(st, dev, ws, nwg);
+    if (bw == 3 && act == GOQ_A8) return launch_stream<3, 1>(st, dev, ws, nwg);
+    if (bw == 4 && act == GOQ_A8) return launch_stream<4, 1>(st, dev, ws, nwg);
+    if (bw == 3 && act == GOQ_A4) return launch_stream<3, 2>(st, dev, ws, nwg);
+    if (bw == 4 && act == GOQ_A4) return launch_stream<4, 2>(st, dev, ws, nwg);
+    return launch_stream<4, 0>(st, dev, ws, nwg);
 }
