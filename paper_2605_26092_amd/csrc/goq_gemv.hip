@@ -60,6 +60,10 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// (explicitly global-memory pointers: generic ones would turn loads into flat loads, which the LDS
+// wait counter has to wait for as well)
+typedef const __attribute__((address_space(1))) uint32_t *gptr;
+typedef const __attribute__((address_space(1))) u32x4 *gptr4;
 
 #ifndef GOQ_WAVES
 #define GOQ_WAVES 8
@@ -74,6 +78,9 @@ constexpr int XG = 1024;                 // bytes of digits per macro-block: 4 k
 constexpr int XZ = 256;                  // zero bytes in front of the digit table
 #ifndef GOQ_CB
 #define GOQ_CB 16
+#endif
+#ifndef GOQ_RING3
+#define GOQ_RING3 0                       // bw = 3: weight stream through an LDS ring (0: register prefetch)
 #endif
 constexpr int CB = GOQ_CB;               // parts a combining wavefront requests at a time
 constexpr int REGIONS = 8;               // static scratch regions: one per stream that launches
@@ -233,11 +240,11 @@ __device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, 
 {
     uint32_t v[4];
     if constexpr (ACT == 0) {
-        const uint4 q = reinterpret_cast<const uint4 *>(x)[(int64_t)g * 16 + r];
+        const u32x4 q = ((gptr4)x)[(int64_t)g * 16 + r];
         v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
     } else if constexpr (ACT == 1) {
-        const uint2 q = reinterpret_cast<const uint2 *>(x)[(int64_t)g * 16 + r];
-        const uint32_t b[2] = {q.x, q.y};
+        const uint32_t b[2] = {((gptr)x)[(int64_t)g * 32 + 2 * r],
+                               ((gptr)x)[(int64_t)g * 32 + 2 * r + 1]};
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const int e0 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1)));
@@ -247,7 +254,7 @@ __device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, 
         }
     } else {
         // packed int4: element i of the run in nibble i of one dword
-        const uint32_t q = reinterpret_cast<const uint32_t *>(x)[(int64_t)g * 16 + r];
+        const uint32_t q = ((gptr)x)[(int64_t)g * 16 + r];
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const int e0 = (int)(q << (28 - 8 * d)) >> 28;         // sign-extended nibble 2 d
@@ -510,13 +517,15 @@ __device__ __forceinline__ void flush(const GemvProblem &P, const Pieces &pc, co
         const float r = __shfl(t, lane & 15);
         if ((lane >> 4) == j) mine = r;
     }
-    if constexpr (ACT != 0) mine *= P.sx[0];
+    if constexpr (ACT != 0) mine *= ((const __attribute__((address_space(1))) float *)P.sx)[0];
     const int rl = wave * GOQ_ROWS + lane;                 // row inside the row group
     const int row = cur.rg * (WAVES * GOQ_ROWS) + rl;
     auto store = [&](float s) {
         if (row < P.out) {
-            if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row] = s;
-            else reinterpret_cast<__half *>(P.y)[row] = __float2half(s);
+            // (global-memory pointers, said explicitly: a generic store may hit LDS as far as the
+            // compiler knows, and every later LDS read would wait for it)
+            if (P.ytype == GOQ_F32) ((__attribute__((address_space(1))) float *)P.y)[row] = s;
+            else ((__attribute__((address_space(1))) unsigned short *)P.y)[row] = __half_as_ushort(__float2half(s));
         }
     };
     if (i0 <= u0 && u1 <= i1) {                            // the whole row group was ours
@@ -630,11 +639,217 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
     }
 }
 
-#define GOQ_GEMV_LDS                                                                        \
-    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];               \
-    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];                     \
-    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];                    \
-    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256]
+// ---- bw = 3: the same loop with the weight stream passing through LDS ---------------------------
+// With the weights prefetched into registers one unit ahead, a wavefront has 4 KiB in flight from
+// its request until the data arrive, then nothing until it has finished the unit it is computing:
+// about 14 MiB in flight chip-wide on average, which at the latency of a loaded HBM (about 2.5 us)
+// caps the stream at 6 TB/s although neither the memory (7 TB/s as a pure read stream of this
+// shape) nor the arithmetic (13 us per LLaMA-2-7B block with the weights in cache) is busy.  More
+// registers per lane there are not.  So the stream goes through LDS instead: each wavefront owns a
+// ring of eight 1 KiB slots (two units); a slice's quads are requested by global_load_lds -- 64
+// lanes x 16 bytes straight into a slot, no registers -- two units before they are used, read back
+// into registers (each lane its own 16 bytes) just before the slice is decoded, and the slot is
+// requested again at once.  Seven of a wavefront's eight slots are in flight at any time, 28 MiB
+// chip-wide.  These requests have no register results, so their waits are written by hand and are
+// exact: when slice j of a unit is needed, the requests younger than its own are the rest of its
+// unit, the whole next unit and the slices of the unit after that already requested -- always
+// seven, and requests return in order.  (Anything else the compiler puts on the same counter can
+// only make such a wait longer, never shorter.)
+constexpr int SWR = 8;                   // units whose activation digits are resident (ring version)
+constexpr int RING_SLOTS = 8;            // 1 KiB slots per wavefront: two units of four slices
+
+// Request slice J of the unit pq points to into slot SLOT of this wavefront's ring (ring_lds: the
+// LDS byte address of the ring, uniform).  The instruction adds its immediate offset to the memory
+// address AND to the LDS address (M0 + offset + 16 * lane), hence the correction in M0.  Issued
+// from inline assembly: the compiler does not know that LDS is written behind its back, and so
+// does not make every later LDS read (digits, exchange table, coefficient bytes) wait for the
+// whole weight stream; the reads of the ring itself follow a hand-written wait.  M0 has no other
+// user in these kernels.
+template <int J, int SLOT>
+__device__ __forceinline__ void ring_request(const gptr4 pq, uint32_t ring_lds)
+{
+    const uint32_t m0 = ring_lds + SLOT * 1024 - J * 256;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2 nt"
+                 :: "v"(pq), "s"(m0), "n"(J * 256) : "memory");
+}
+
+template <int YOUNGER>
+__device__ __forceinline__ void ring_wait()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
+}
+
+// One unit (64 rows x one macro-block) out of ring half HALF.  REQ: every slot is requested again
+// (slice j of the unit `refill` points to, two units ahead) as soon as it has been read.  Without
+// REQ (the last two units of a piece) the caller has waited for everything.
+template <bool REQ, int HALF>
+__device__ __forceinline__ void compute_unit_ring(const unsigned char *ring_wave, uint32_t ring_lds, const gptr4 refill, uint32_t vt, const v8i &A,
+                                                  int sa, unsigned char *cwx, int lane, float (&acc)[4])
+{
+    const int c = lane & 15, q = lane >> 4;
+    const int cpos = coefficient_byte_position<3>(q);
+    v4f D1[2], D2[2];
+    auto slice = [&](auto jt) {
+        constexpr int j = decltype(jt)::value;
+        constexpr int slot = 4 * HALF + j;
+        if constexpr (REQ) ring_wait<7>();
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(ring_wave + slot * 1024 + lane * 16);
+        const uint4 quad = make_uint4(v.x, v.y, v.z, v.w);
+        cwx[j * 64 + c * 4 + cpos] = (unsigned char)coefficient_byte<3>(quad, 0u);
+        asm volatile("" ::: "memory");
+        slice_products<3>(quad, 0u, vt, A, sa, D1[j & 1], D2[j & 1]);
+        // (the slot's old content is in registers: the decode above has consumed `quad`)
+        if constexpr (REQ) ring_request<j, slot>(refill, ring_lds);
+        if constexpr (j > 0) {
+            const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + (j - 1) * 64 + c * 4);
+            acc[j - 1] = rescale(cword, D1[(j - 1) & 1], D2[(j - 1) & 1], acc[j - 1]);
+        }
+    };
+    slice(std::integral_constant<int, 0>{});
+    slice(std::integral_constant<int, 1>{});
+    slice(std::integral_constant<int, 2>{});
+    slice(std::integral_constant<int, 3>{});
+    const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + 3 * 64 + c * 4);
+    acc[3] = rescale(cword, D1[1], D2[1], acc[3]);
+}
+
+template <int ACT, bool TABLE>
+__device__ __forceinline__ void stream_piece_ring(const Problems<TABLE> &pb, const Pieces &pc, int i0, int i1, Cursor cur,
+                                                  unsigned char *xtab, unsigned char *stab, unsigned char *vtab,
+                                                  unsigned char *cwx, unsigned char *ring)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const unsigned char *ring_wave = ring + wave * (RING_SLOTS * 1024);
+    const uint32_t ring_lds = (uint32_t)uniform((int)(uint32_t)(uintptr_t)(const __attribute__((address_space(3))) unsigned char *)ring_wave);
+
+    // F: the position of the next unit to request (F.idx == idx + 2 in the steady state).  The
+    // first two units are requested before anything else.
+    struct Fetch {
+        Cursor c;
+        const uint32_t *packed;
+        int gn, rbn, rgroups, idx;
+    } F;
+    Stream S = stream_of(pb, cur.pi);
+    F.c = cur;
+    F.packed = S.packed;
+    F.gn = S.gn;
+    F.rbn = S.rbn;
+    F.rgroups = S.rgroups;
+    F.idx = i0;
+    // the lane's pointer to its quad of slice 0 of unit F.idx (a wavefront without rows of its own in
+    // that row group requests the group's last row block: every wavefront issues the same requests)
+    auto fetch_ptr = [&]() -> gptr4 {
+        const int64_t R = min(F.c.rg * WAVES + wave, F.rbn - 1);
+        gptr base = (gptr)F.packed + (R * F.gn + F.c.g) * (4 * GOQ_ROWS * 4);
+        return (gptr4)(base + (lane >> 4) * (GOQ_ROWS * 4) + (lane & 15) * 4);
+    };
+    auto fetch_advance = [&]() {
+        ++F.idx;
+        if (++F.c.g == F.gn) {
+            F.c.g = 0;
+            if (++F.c.rg == F.rgroups) {
+                F.c.rg = 0;
+                ++F.c.pi;
+                if (F.idx < i1) {
+                    const Stream Sf = stream_of(pb, F.c.pi);
+                    F.packed = Sf.packed;
+                    F.gn = Sf.gn;
+                    F.rbn = Sf.rbn;
+                    F.rgroups = Sf.rgroups;
+                }
+            }
+        }
+    };
+    {
+        const gptr4 p0 = fetch_ptr();
+        ring_request<0, 0>(p0, ring_lds);
+        ring_request<1, 1>(p0, ring_lds);
+        ring_request<2, 2>(p0, ring_lds);
+        ring_request<3, 3>(p0, ring_lds);
+        if (i0 + 1 < i1) {
+            fetch_advance();
+            const gptr4 p1 = fetch_ptr();
+            ring_request<0, 4>(p1, ring_lds);
+            ring_request<1, 5>(p1, ring_lds);
+            ring_request<2, 6>(p1, ring_lds);
+            ring_request<3, 7>(p1, ring_lds);
+        }
+        fetch_advance();
+    }
+
+    for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
+    if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
+
+    const int arow = lane & 15, q = lane >> 4;
+    const bool arow_live = (arow & 3) < 2;
+    const int digit = 2 * (arow >> 2) + (arow & 1);
+    const uint32_t abase = arow_live ? (uint32_t)(XZ + q * 256 + digit * 32) : 0u;
+    const uint32_t amask = arow_live ? ~0u : 0u;
+    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane & 3) * 16;
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    int idx = i0;
+    auto step = [&](auto req_tag, auto half_tag) {
+        constexpr bool REQ = decltype(req_tag)::value;
+        constexpr int HALF = decltype(half_tag)::value;
+        const int slot = (idx - i0) % SWR;
+        if (slot == 0) {
+            if (idx != i0) __syncthreads();                    // everyone is done with the old window
+            stage_window<ACT, TABLE>(pb, cur.pi, S.end, idx, min(SWR, i1 - idx), xtab + XZ, stab, tid);
+            __syncthreads();
+        }
+        gptr4 refill = nullptr;
+        if constexpr (REQ) refill = fetch_ptr();
+        else ring_wait<0>();                                   // the last two units: nothing is requested any more
+        const int R = cur.rg * WAVES + wave;
+        const bool live = R < S.rbn;
+        if (live) {
+            const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
+            const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
+            const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * digit;    // digit i sits 3 i places lower
+            compute_unit_ring<REQ, HALF>(ring_wave, ring_lds, refill, vt_lane, A, sa, cwx + wave * 256, lane, acc);
+        } else if constexpr (REQ) {
+            // no rows of its own in this row group: the same four requests, nothing to compute
+            ring_request<0, 4 * HALF + 0>(refill, ring_lds);
+            ring_request<1, 4 * HALF + 1>(refill, ring_lds);
+            ring_request<2, 4 * HALF + 2>(refill, ring_lds);
+            ring_request<3, 4 * HALF + 3>(refill, ring_lds);
+        }
+        if constexpr (REQ) fetch_advance();
+        const bool last = idx + 1 == i1;
+        Cursor nxt = cur;
+        if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
+        if (last || nxt.rg != cur.rg || nxt.pi != cur.pi) {
+            if (live) flush<ACT>(pb[cur.pi], pc, cur, acc, i0, i1, wave, lane);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = 0.f;
+        }
+        if (!last && nxt.pi != cur.pi) S = stream_of(pb, nxt.pi);
+        cur = nxt;
+        ++idx;
+    };
+    const std::true_type REQ{};
+    const std::false_type NOREQ{};
+    const std::integral_constant<int, 0> H0{};
+    const std::integral_constant<int, 1> H1{};
+    while (true) {
+        if (idx + 2 < i1) step(REQ, H0);
+        else { step(NOREQ, H0); if (idx < i1) step(NOREQ, H1); break; }
+        if (idx + 2 < i1) step(REQ, H1);
+        else { step(NOREQ, H1); if (idx < i1) step(NOREQ, H0); break; }
+    }
+}
+
+// LDS of the streaming kernels: the digit window (bw = 3: SWR units, and the weight ring beside it)
+#define GOQ_GEMV_LDS                                                                                        \
+    constexpr bool RING = (BW == 3) && GOQ_RING3;                                                           \
+    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + (RING ? SWR : SW) * XG];                \
+    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];                                     \
+    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];                                    \
+    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256];                                 \
+    __shared__ __attribute__((aligned(1024))) unsigned char wring[RING ? WAVES * RING_SLOTS * 1024 : 1024]
 
 // Problems in the kernel arguments.  The leading scalar arguments repeat what the first
 // instructions of a workgroup need -- the piece sizes and the first unit of every problem -- as
@@ -672,7 +887,8 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
     }
     const Problems<false> pb{a};
     const Pieces pc{pq, pr, a.scratch};
-    stream_piece<BW, ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
+    if constexpr (RING) stream_piece_ring<ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx, wring);
+    else stream_piece<BW, ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
 }
 
 // Problems in a table in device memory (goq_gemv_stream).
@@ -696,7 +912,8 @@ void gemv_stream_kernel(const GemvTable *__restrict__ T, Region *ws)
         cur.g = uniform(local % gn);
     }
     const Pieces pc{pq, pr, ws};
-    stream_piece<BW, ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
+    if constexpr (RING) stream_piece_ring<ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx, wring);
+    else stream_piece<BW, ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
 }
 
 // Zero-fill of a caller-owned workspace (a kernel, not a memset node, so that a caller may
@@ -815,11 +1032,13 @@ void gemv_rows_kernel(GemvArgs a)
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < NT / 16; ++i) s += red[i * 16 + tid];
-        if constexpr (ACT != 0) s *= P.sx[0];
+        if constexpr (ACT != 0) s *= ((const __attribute__((address_space(1))) float *)P.sx)[0];
         const int row = R * GOQ_ROWS + 16 * j + tid;
         if (row < P.out) {
-            if (P.ytype == GOQ_F32) reinterpret_cast<float *>(P.y)[row] = s;
-            else reinterpret_cast<__half *>(P.y)[row] = __float2half(s);
+            // (global-memory pointers, said explicitly: a generic store may hit LDS as far as the
+            // compiler knows, and every later LDS read would wait for it)
+            if (P.ytype == GOQ_F32) ((__attribute__((address_space(1))) float *)P.y)[row] = s;
+            else ((__attribute__((address_space(1))) unsigned short *)P.y)[row] = __half_as_ushort(__float2half(s));
         }
     }
 }
