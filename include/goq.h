@@ -133,7 +133,17 @@ int goq_gemv(void *stream, int bw, int act, int64_t out, int64_t in,
              const void *packed, const void *x, const float *sx, void *y, int ytype);
 
 /* Several independent batch-1 layers in ONE launch (e.g. the projections of a decoder block).
- * descs is a HOST array of n <= GOQ_MAX_BATCH descriptors; all must share bw and act. */
+ * descs is a HOST array of n <= GOQ_MAX_BATCH descriptors; all must share bw and act.
+ * This is the entry point for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid it): like goq_gemv it allocates nothing and
+ * takes no workspace -- its scratch for split row groups is the library's static device array
+ * described at goq_gemv (8 regions of 2.1 MB, held on every device the library runs on until the
+ * process ends; its device address is resolved once per device on the first call).  The array
+ * suffices for every accepted shape (the launch never has more than 512 workgroups, whatever the
+ * layers' sizes), so no size is rejected on its account.  It keeps the previous launch's contents:
+ * the arrival counters are back at zero when a launch has completed, the parts are overwritten
+ * before they are read.  Launches that overlap on one region would race: the library gives every
+ * stream a region of its own (see goq_gemv for the limit of 8 streams). */
 typedef struct goq_gemv_desc {
     int64_t out, in;
     const void *packed;
