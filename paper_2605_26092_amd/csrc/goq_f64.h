@@ -1,5 +1,5 @@
 // fp64 helpers shared by the calibration-time kernels (quantizer, REF coefficients): exact
-// fp16 <-> fp64 conversion and the value of a canonical lattice code.
+// fp16 -> fp64 conversion, fp64 -> fp16 rounding and the value of a canonical lattice code.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -10,25 +10,31 @@ __device__ __forceinline__ double half_bits_to_double(uint32_t h)
     return (double)(float)__builtin_bit_cast(_Float16, (unsigned short)h);
 }
 
-// round-to-nearest-even from fp64 straight to binary16 (no intermediate fp32)
+// fp64 -> IEEE binary16 bits, round to nearest even, straight from the bit pattern (no
+// intermediate fp32): the 53-bit significand is cut at the binary16 quantum of its binade (2^-24
+// below 2^-14) and the cut-off part is compared with half a quantum.
 __device__ __forceinline__ uint32_t double_to_half_bits(double d)
 {
-    const uint32_t sign = (__double_as_longlong(d) < 0) ? 0x8000u : 0u;
-    const double a = fabs(d);
-    if (d != d) return 0x7e00u;
-    if (a >= 65520.0) return sign | 0x7c00u;                    // rounds to infinity
-    if (a == 0.0) return sign;
-    int e;
-    (void)frexp(a, &e);                                         // a = f 2^e, f in [0.5, 1)
-    int ex = e - 1;
-    if (ex < -14) ex = -14;                                     // subnormal range: fixed quantum 2^-24
-    const double q = ldexp(a, 10 - ex);                         // in units of 2^(ex-10); exact
-    int m = (int)rint(q);                                       // ties to even; in [0, 2048]
-    int be = ex + 15;
-    if (ex == -14 && m < 1024) return sign | (uint32_t)m;       // subnormal (or zero)
-    if (m == 2048) { m = 1024; be += 1; }
-    if (be >= 31) return sign | 0x7c00u;
-    return sign | (uint32_t)(be << 10) | (uint32_t)(m & 0x3ff);
+    const uint64_t u = (uint64_t)__double_as_longlong(d);
+    const uint32_t sign = (uint32_t)(u >> 48) & 0x8000u;
+    const int ex = (int)((u >> 52) & 0x7ff);
+    const uint64_t frac = u & 0xfffffffffffffull;
+    if (ex == 0x7ff) return sign | (frac ? 0x7e00u : 0x7c00u);
+    if (ex == 0) return sign;                                   // fp64 subnormals are far below 2^-25
+    const int e = ex - 1023;
+    if (e > 15) return sign | 0x7c00u;
+    const uint64_t sig = frac | (1ull << 52);                   // 1.f as a 53-bit integer, value sig 2^(e-52)
+    int drop = 42;                                              // bits below the quantum 2^(e-10)
+    if (e < -14) drop += -14 - e;                               // subnormal range: quantum 2^-24
+    if (drop > 54) return sign;                                 // below a quarter quantum: zero
+    const uint64_t q = sig >> drop;
+    const uint64_t rem = sig & ((1ull << drop) - 1), halfq = 1ull << (drop - 1);
+    const uint32_t up = (rem > halfq || (rem == halfq && (q & 1))) ? 1u : 0u;
+    // normal: q in [1024, 2047] carries the implicit bit, which lands on the exponent field;
+    // subnormal: q < 1024 is the fraction itself.  A carry out of the fraction bumps the exponent
+    // by plain addition (2047 + 1 -> next binade, 1023 + 1 -> smallest normal, 31 << 10 -> infinity).
+    const uint32_t base = (e < -14) ? 0u : (uint32_t)(e + 14) << 10;
+    return sign | (base + (uint32_t)q + up);
 }
 
 // value of one canonical code: (-1)^sign 2^-e, (sign 0, e = E - 1) is exact zero (Sec. 3.2)
