@@ -48,6 +48,7 @@
 #include <atomic>
 #include <mutex>
 #include <string.h>
+#include <stddef.h>
 #include <stdio.h>
 #include <type_traits>
 #include "goq_layout.h"
@@ -79,9 +80,11 @@ constexpr int XZ = 256;                  // zero bytes in front of the digit tab
 #ifndef GOQ_CB
 #define GOQ_CB 16
 #endif
-#ifndef GOQ_RING3
-#define GOQ_RING3 0                       // bw = 3: weight stream through an LDS ring (0: register prefetch)
+#ifndef GOQ_VCOPIES
+#define GOQ_VCOPIES 16
 #endif
+constexpr int VC = GOQ_VCOPIES;          // copies of the exchange table in LDS (a lane uses copy lane % VC)
+constexpr int VS = VC * 16;              // bytes from one entry to the next
 constexpr int CB = GOQ_CB;               // parts a combining wavefront requests at a time
 constexpr int REGIONS = 8;               // static scratch regions: one per stream that launches
 
@@ -135,11 +138,15 @@ struct GemvTable {
 // table in device memory.
 template <bool TABLE>
 struct Problems;
+// (Kernel arguments are read through the kernel-argument segment pointer: indexing the by-value
+// argument struct with a run-time index inside loops makes the compiler copy it to scratch.)
 template <>
 struct Problems<false> {
-    const GemvArgs &a;
-    __device__ __forceinline__ const GemvProblem &operator[](int i) const { return a.p[i]; }
-    __device__ __forceinline__ int n() const { return a.n; }
+    typedef const __attribute__((address_space(4))) GemvProblem Entry;
+    Entry *t;
+    int cnt;
+    __device__ __forceinline__ Entry &operator[](int i) const { return t[i]; }
+    __device__ __forceinline__ int n() const { return cnt; }
 };
 template <>
 struct Problems<true> {
@@ -235,26 +242,24 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ packed, i
 // macro-block: the 32 bytes of (k-group h, digit i) at h * 256 + i * 32; scale byte (E + 110) of
 // block Q at st[Q], where E + 15 is the largest biased fp16 exponent of the block (subnormals
 // count as 1).
+// The 8 activations of run r as four registers of two fp16 each, from the run's raw words:
+// raw[0..3] (fp16), raw[0..1] (int8) or raw[0] (packed int4: element i in nibble i).  Integer
+// activations are exact in fp16.
 template <int ACT>
-__device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, const void *x, int g, int r)
+__device__ __forceinline__ void run_as_half(const uint32_t (&raw)[4], uint32_t (&v)[4])
 {
-    uint32_t v[4];
     if constexpr (ACT == 0) {
-        const u32x4 q = ((gptr4)x)[(int64_t)g * 16 + r];
-        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        v[0] = raw[0]; v[1] = raw[1]; v[2] = raw[2]; v[3] = raw[3];
     } else if constexpr (ACT == 1) {
-        const uint32_t b[2] = {((gptr)x)[(int64_t)g * 32 + 2 * r],
-                               ((gptr)x)[(int64_t)g * 32 + 2 * r + 1]};
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
-            const int e0 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1)));
-            const int e1 = (int)(int8_t)(b[d >> 1] >> (16 * (d & 1) + 8));
+            const int e0 = (int)(int8_t)(raw[d >> 1] >> (16 * (d & 1)));
+            const int e1 = (int)(int8_t)(raw[d >> 1] >> (16 * (d & 1) + 8));
             const goq_half2 hv = {(_Float16)e0, (_Float16)e1};     // exact: |e| <= 128
             v[d] = __builtin_bit_cast(uint32_t, hv);
         }
     } else {
-        // packed int4: element i of the run in nibble i of one dword
-        const uint32_t q = ((gptr)x)[(int64_t)g * 16 + r];
+        const uint32_t q = raw[0];
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const int e0 = (int)(q << (28 - 8 * d)) >> 28;         // sign-extended nibble 2 d
@@ -263,6 +268,45 @@ __device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, 
             v[d] = __builtin_bit_cast(uint32_t, hv);
         }
     }
+}
+
+// bytes of one macro-block's activations in memory
+template <int ACT>
+constexpr int unit_x_bytes() { return ACT == 0 ? 256 : ACT == 1 ? 128 : 64; }
+
+// run r of macro-block g of x in global memory
+template <int ACT>
+__device__ __forceinline__ void load_run(const void *x, int g, int r, uint32_t (&raw)[4])
+{
+    raw[0] = raw[1] = raw[2] = raw[3] = 0u;
+    if constexpr (ACT == 0) {
+        const u32x4 q = ((gptr4)x)[(int64_t)g * 16 + r];
+        raw[0] = q.x; raw[1] = q.y; raw[2] = q.z; raw[3] = q.w;
+    } else if constexpr (ACT == 1) {
+        raw[0] = ((gptr)x)[(int64_t)g * 32 + 2 * r];
+        raw[1] = ((gptr)x)[(int64_t)g * 32 + 2 * r + 1];
+    } else {
+        raw[0] = ((gptr)x)[(int64_t)g * 16 + r];
+    }
+}
+
+template <int ACT>
+__device__ __forceinline__ void stage_digits(unsigned char *xt, unsigned char *st, const uint32_t (&raw)[4], int r);
+
+template <int ACT>
+__device__ __forceinline__ void stage_run(unsigned char *xt, unsigned char *st, const void *x, int g, int r)
+{
+    uint32_t raw[4];
+    load_run<ACT>(x, g, r, raw);
+    stage_digits<ACT>(xt, st, raw, r);
+}
+
+// digit table and block scales of one run (see above) from its raw words
+template <int ACT>
+__device__ __forceinline__ void stage_digits(unsigned char *xt, unsigned char *st, const uint32_t (&raw)[4], int r)
+{
+    uint32_t v[4];
+    run_as_half<ACT>(raw, v);
     // largest biased exponent of the run (subnormals count as 1), then of the scale block
     int emax = 1;
 #pragma unroll
@@ -323,21 +367,38 @@ struct Cursor {
 // registers.  end: first unit of the next problem.
 struct Stream {
     const uint32_t *packed;
-    int gn, rbn, rgroups, end;
+    void *y;
+    const float *sx;
+    int gn, rbn, rgroups, begin, end, out, ytype;
 };
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-template <bool TABLE>
+template <typename Fields>
+__device__ __forceinline__ void output_fields(Stream &s, const Fields &P)
+{
+    const uint64_t py = (uint64_t)P.y, ps = (uint64_t)P.sx;
+    s.y = (void *)(((uint64_t)(uint32_t)uniform((int)(py >> 32)) << 32) | (uint32_t)uniform((int)py));
+    s.sx = (const float *)(((uint64_t)(uint32_t)uniform((int)(ps >> 32)) << 32) | (uint32_t)uniform((int)ps));
+    s.out = uniform(P.out);
+    s.ytype = uniform(P.ytype);
+}
+
+// OUTPUT: also the fields the end of a row group needs (bw = 3 keeps them in scalar registers for
+// the whole problem, so that a row group ends without a memory round trip; bw = 4 has no registers
+// to spare and reads them when a row group ends).
+template <bool OUTPUT, bool TABLE>
 __device__ __forceinline__ Stream stream_of(const Problems<TABLE> &pb, int pi)
 {
     Stream s;
-    const GemvProblem &P = pb[pi];
+    const auto &P = pb[pi];
+    if constexpr (OUTPUT) output_fields(s, P);
     const uint64_t pk = (uint64_t)P.packed;
     s.packed = (const uint32_t *)(((uint64_t)(uint32_t)uniform((int)(pk >> 32)) << 32) | (uint32_t)uniform((int)pk));
     s.gn = uniform(P.gn);
     s.rbn = uniform(P.rbn);
     s.rgroups = uniform(P.rgroups);
+    s.begin = uniform(P.begin);
     s.end = uniform(P.begin + P.rgroups * P.gn);
     return s;
 }
@@ -357,7 +418,7 @@ __device__ __forceinline__ void stage_window(const Problems<TABLE> &pb, int pi0,
             ++pi;
             while (pi + 1 < pb.n() && u >= pb[pi + 1].begin) ++pi;
         }
-        const GemvProblem &P = pb[pi];
+        const auto &P = pb[pi];
         stage_run<ACT>(xt + slot * XG, st + slot * 4, P.x, (u - P.begin) % P.gn, tid & 15);
     }
 }
@@ -379,13 +440,14 @@ __device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t md, u
     constexpr int LA = (BW == 3) ? 4 : 2;
     u32x4 ev[4];
     auto request = [&](int k) {
-        uint32_t eo;                       // LDS address of the entry: vt + 64 * (pattern | signs << 2)
+        uint32_t eo;                       // LDS address of the entry: vt + VS * (pattern | signs << 2)
         if constexpr (BW == 3) {
             // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
-            // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2)
-            eo = __builtin_amdgcn_udot4(dw[k] & 0x00C0C0C0u, 0x00100401u, vt, false);
+            // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2); the weights
+            // are scaled to the entry stride VS
+            eo = __builtin_amdgcn_udot4(dw[k] & 0x00C0C0C0u, 0x00100401u * (VS / 64), vt, false);
         } else {
-            eo = vt + (((md >> (6 * k)) & 63u) << 6);
+            eo = vt + ((md >> (6 * k)) & 63u) * VS;
         }
         ev[k] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
     };
@@ -502,8 +564,9 @@ __device__ __forceinline__ int piece_of(const Pieces &pc, int u)
 // totally ordered at the counter, so the reader's loads come after all the stores.  This is a
 // release (stores, wait, add) / acquire (add, loads) pair built from per-access scopes instead of
 // fences: an agent-scope release FENCE would write back the whole L2 for 256 bytes of parts.
-template <int ACT>
-__device__ __forceinline__ void flush(const GemvProblem &P, const Pieces &pc, const Cursor &cur, float (&acc)[4],
+// P: the problem's fields, from the table (GemvProblem) or from scalar registers (Stream).
+template <int ACT, typename Fields>
+__device__ __forceinline__ void flush(const Fields &P, const Pieces &pc, const Cursor &cur, float (&acc)[4],
                                       int i0, int i1, int wave, int lane)
 {
     const int u0 = P.begin + cur.rg * P.gn, u1 = u0 + P.gn;
@@ -564,7 +627,8 @@ __device__ __forceinline__ void flush(const GemvProblem &P, const Pieces &pc, co
 // ---- the streaming loop of one workgroup over its piece [i0, i1) ------------------------------
 // cur: the position of unit i0.  LDS: xtab = zeros (the A rows without a digit), then the digit
 // table of the resident units; stab = its block scales; vtab = exchange table, entry v at
-// 64 v + 16 r, four copies r (a lane uses copy lane % 4); cwx = coefficient-byte exchange.
+// VS v + 16 r, VC copies r (lane l reads copy l % 16: the 16 lanes of a 128-bit LDS read then hit 16
+// different bank groups whatever their entries v are); cwx = coefficient-byte exchange.
 template <int BW, int ACT, bool TABLE>
 __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pieces &pc, int i0, int i1, Cursor cur,
                                              unsigned char *xtab, unsigned char *stab, unsigned char *vtab,
@@ -576,10 +640,11 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
 
     // the first unit's weights are requested before anything else
     UnitBuf<BW> bufA, bufB;
-    Stream S = stream_of(pb, cur.pi);
+    constexpr bool KEEP = (BW == 3);
+    Stream S = stream_of<KEEP>(pb, cur.pi);
     load_unit<BW>(S.packed, S.gn, min(cur.rg * WAVES + wave, S.rbn - 1), cur.g, lane, bufA);
 
-    for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
+    for (int t = tid; t < 64 * VC; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t / VC);
     if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
 
     // A operand of this lane: row = lane % 16, k-group q = lane / 16.  Digit d sits in row
@@ -590,7 +655,7 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
     const int digit = 2 * (arow >> 2) + (arow & 1);
     const uint32_t abase = arow_live ? (uint32_t)(XZ + q * 256 + digit * 32) : 0u;
     const uint32_t amask = arow_live ? ~0u : 0u;
-    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane & 3) * 16;
+    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane % VC) * 16;
 
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     int idx = i0;
@@ -611,7 +676,7 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
         if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
         Stream Sn = S;
         if constexpr (MORE) {
-            if (nxt.pi != cur.pi) Sn = stream_of(pb, nxt.pi);
+            if (nxt.pi != cur.pi) Sn = stream_of<KEEP>(pb, nxt.pi);
             load_unit<BW>(Sn.packed, Sn.gn, min(nxt.rg * WAVES + wave, Sn.rbn - 1), nxt.g, lane, bnxt);
         }
         const int R = cur.rg * WAVES + wave;
@@ -623,7 +688,10 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
             compute_unit<BW>(bcur, vt_lane, A, sa, cwx + wave * 256, lane, acc);
         }
         if (!MORE || nxt.rg != cur.rg || nxt.pi != cur.pi) {
-            if (live) flush<ACT>(pb[cur.pi], pc, cur, acc, i0, i1, wave, lane);
+            if (live) {
+                if constexpr (KEEP) flush<ACT>(S, pc, cur, acc, i0, i1, wave, lane);
+                else flush<ACT>(pb[cur.pi], pc, cur, acc, i0, i1, wave, lane);
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[j] = 0.f;
         }
@@ -639,217 +707,12 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
     }
 }
 
-// ---- bw = 3: the same loop with the weight stream passing through LDS ---------------------------
-// With the weights prefetched into registers one unit ahead, a wavefront has 4 KiB in flight from
-// its request until the data arrive, then nothing until it has finished the unit it is computing:
-// about 14 MiB in flight chip-wide on average, which at the latency of a loaded HBM (about 2.5 us)
-// caps the stream at 6 TB/s although neither the memory (7 TB/s as a pure read stream of this
-// shape) nor the arithmetic (13 us per LLaMA-2-7B block with the weights in cache) is busy.  More
-// registers per lane there are not.  So the stream goes through LDS instead: each wavefront owns a
-// ring of eight 1 KiB slots (two units); a slice's quads are requested by global_load_lds -- 64
-// lanes x 16 bytes straight into a slot, no registers -- two units before they are used, read back
-// into registers (each lane its own 16 bytes) just before the slice is decoded, and the slot is
-// requested again at once.  Seven of a wavefront's eight slots are in flight at any time, 28 MiB
-// chip-wide.  These requests have no register results, so their waits are written by hand and are
-// exact: when slice j of a unit is needed, the requests younger than its own are the rest of its
-// unit, the whole next unit and the slices of the unit after that already requested -- always
-// seven, and requests return in order.  (Anything else the compiler puts on the same counter can
-// only make such a wait longer, never shorter.)
-constexpr int SWR = 8;                   // units whose activation digits are resident (ring version)
-constexpr int RING_SLOTS = 8;            // 1 KiB slots per wavefront: two units of four slices
-
-// Request slice J of the unit pq points to into slot SLOT of this wavefront's ring (ring_lds: the
-// LDS byte address of the ring, uniform).  The instruction adds its immediate offset to the memory
-// address AND to the LDS address (M0 + offset + 16 * lane), hence the correction in M0.  Issued
-// from inline assembly: the compiler does not know that LDS is written behind its back, and so
-// does not make every later LDS read (digits, exchange table, coefficient bytes) wait for the
-// whole weight stream; the reads of the ring itself follow a hand-written wait.  M0 has no other
-// user in these kernels.
-template <int J, int SLOT>
-__device__ __forceinline__ void ring_request(const gptr4 pq, uint32_t ring_lds)
-{
-    const uint32_t m0 = ring_lds + SLOT * 1024 - J * 256;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2 nt"
-                 :: "v"(pq), "s"(m0), "n"(J * 256) : "memory");
-}
-
-template <int YOUNGER>
-__device__ __forceinline__ void ring_wait()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
-}
-
-// One unit (64 rows x one macro-block) out of ring half HALF.  REQ: every slot is requested again
-// (slice j of the unit `refill` points to, two units ahead) as soon as it has been read.  Without
-// REQ (the last two units of a piece) the caller has waited for everything.
-template <bool REQ, int HALF>
-__device__ __forceinline__ void compute_unit_ring(const unsigned char *ring_wave, uint32_t ring_lds, const gptr4 refill, uint32_t vt, const v8i &A,
-                                                  int sa, unsigned char *cwx, int lane, float (&acc)[4])
-{
-    const int c = lane & 15, q = lane >> 4;
-    const int cpos = coefficient_byte_position<3>(q);
-    v4f D1[2], D2[2];
-    auto slice = [&](auto jt) {
-        constexpr int j = decltype(jt)::value;
-        constexpr int slot = 4 * HALF + j;
-        if constexpr (REQ) ring_wait<7>();
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(ring_wave + slot * 1024 + lane * 16);
-        const uint4 quad = make_uint4(v.x, v.y, v.z, v.w);
-        cwx[j * 64 + c * 4 + cpos] = (unsigned char)coefficient_byte<3>(quad, 0u);
-        asm volatile("" ::: "memory");
-        slice_products<3>(quad, 0u, vt, A, sa, D1[j & 1], D2[j & 1]);
-        // (the slot's old content is in registers: the decode above has consumed `quad`)
-        if constexpr (REQ) ring_request<j, slot>(refill, ring_lds);
-        if constexpr (j > 0) {
-            const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + (j - 1) * 64 + c * 4);
-            acc[j - 1] = rescale(cword, D1[(j - 1) & 1], D2[(j - 1) & 1], acc[j - 1]);
-        }
-    };
-    slice(std::integral_constant<int, 0>{});
-    slice(std::integral_constant<int, 1>{});
-    slice(std::integral_constant<int, 2>{});
-    slice(std::integral_constant<int, 3>{});
-    const uint32_t cword = *reinterpret_cast<const uint32_t *>(cwx + 3 * 64 + c * 4);
-    acc[3] = rescale(cword, D1[1], D2[1], acc[3]);
-}
-
-template <int ACT, bool TABLE>
-__device__ __forceinline__ void stream_piece_ring(const Problems<TABLE> &pb, const Pieces &pc, int i0, int i1, Cursor cur,
-                                                  unsigned char *xtab, unsigned char *stab, unsigned char *vtab,
-                                                  unsigned char *cwx, unsigned char *ring)
-{
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = uniform(tid >> 6);
-    const unsigned char *ring_wave = ring + wave * (RING_SLOTS * 1024);
-    const uint32_t ring_lds = (uint32_t)uniform((int)(uint32_t)(uintptr_t)(const __attribute__((address_space(3))) unsigned char *)ring_wave);
-
-    // F: the position of the next unit to request (F.idx == idx + 2 in the steady state).  The
-    // first two units are requested before anything else.
-    struct Fetch {
-        Cursor c;
-        const uint32_t *packed;
-        int gn, rbn, rgroups, idx;
-    } F;
-    Stream S = stream_of(pb, cur.pi);
-    F.c = cur;
-    F.packed = S.packed;
-    F.gn = S.gn;
-    F.rbn = S.rbn;
-    F.rgroups = S.rgroups;
-    F.idx = i0;
-    // the lane's pointer to its quad of slice 0 of unit F.idx (a wavefront without rows of its own in
-    // that row group requests the group's last row block: every wavefront issues the same requests)
-    auto fetch_ptr = [&]() -> gptr4 {
-        const int64_t R = min(F.c.rg * WAVES + wave, F.rbn - 1);
-        gptr base = (gptr)F.packed + (R * F.gn + F.c.g) * (4 * GOQ_ROWS * 4);
-        return (gptr4)(base + (lane >> 4) * (GOQ_ROWS * 4) + (lane & 15) * 4);
-    };
-    auto fetch_advance = [&]() {
-        ++F.idx;
-        if (++F.c.g == F.gn) {
-            F.c.g = 0;
-            if (++F.c.rg == F.rgroups) {
-                F.c.rg = 0;
-                ++F.c.pi;
-                if (F.idx < i1) {
-                    const Stream Sf = stream_of(pb, F.c.pi);
-                    F.packed = Sf.packed;
-                    F.gn = Sf.gn;
-                    F.rbn = Sf.rbn;
-                    F.rgroups = Sf.rgroups;
-                }
-            }
-        }
-    };
-    {
-        const gptr4 p0 = fetch_ptr();
-        ring_request<0, 0>(p0, ring_lds);
-        ring_request<1, 1>(p0, ring_lds);
-        ring_request<2, 2>(p0, ring_lds);
-        ring_request<3, 3>(p0, ring_lds);
-        if (i0 + 1 < i1) {
-            fetch_advance();
-            const gptr4 p1 = fetch_ptr();
-            ring_request<0, 4>(p1, ring_lds);
-            ring_request<1, 5>(p1, ring_lds);
-            ring_request<2, 6>(p1, ring_lds);
-            ring_request<3, 7>(p1, ring_lds);
-        }
-        fetch_advance();
-    }
-
-    for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
-    if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
-
-    const int arow = lane & 15, q = lane >> 4;
-    const bool arow_live = (arow & 3) < 2;
-    const int digit = 2 * (arow >> 2) + (arow & 1);
-    const uint32_t abase = arow_live ? (uint32_t)(XZ + q * 256 + digit * 32) : 0u;
-    const uint32_t amask = arow_live ? ~0u : 0u;
-    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane & 3) * 16;
-
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    int idx = i0;
-    auto step = [&](auto req_tag, auto half_tag) {
-        constexpr bool REQ = decltype(req_tag)::value;
-        constexpr int HALF = decltype(half_tag)::value;
-        const int slot = (idx - i0) % SWR;
-        if (slot == 0) {
-            if (idx != i0) __syncthreads();                    // everyone is done with the old window
-            stage_window<ACT, TABLE>(pb, cur.pi, S.end, idx, min(SWR, i1 - idx), xtab + XZ, stab, tid);
-            __syncthreads();
-        }
-        gptr4 refill = nullptr;
-        if constexpr (REQ) refill = fetch_ptr();
-        else ring_wait<0>();                                   // the last two units: nothing is requested any more
-        const int R = cur.rg * WAVES + wave;
-        const bool live = R < S.rbn;
-        if (live) {
-            const v8i A = *reinterpret_cast<const v8i *>(xtab + abase + ((uint32_t)(slot * XG) & amask));
-            const uint32_t sc = *reinterpret_cast<const uint32_t *>(stab + slot * 4);
-            const int sa = (int)((sc >> (8 * q)) & 0xFFu) - 3 * digit;    // digit i sits 3 i places lower
-            compute_unit_ring<REQ, HALF>(ring_wave, ring_lds, refill, vt_lane, A, sa, cwx + wave * 256, lane, acc);
-        } else if constexpr (REQ) {
-            // no rows of its own in this row group: the same four requests, nothing to compute
-            ring_request<0, 4 * HALF + 0>(refill, ring_lds);
-            ring_request<1, 4 * HALF + 1>(refill, ring_lds);
-            ring_request<2, 4 * HALF + 2>(refill, ring_lds);
-            ring_request<3, 4 * HALF + 3>(refill, ring_lds);
-        }
-        if constexpr (REQ) fetch_advance();
-        const bool last = idx + 1 == i1;
-        Cursor nxt = cur;
-        if (++nxt.g == S.gn) { nxt.g = 0; if (++nxt.rg == S.rgroups) { nxt.rg = 0; ++nxt.pi; } }
-        if (last || nxt.rg != cur.rg || nxt.pi != cur.pi) {
-            if (live) flush<ACT>(pb[cur.pi], pc, cur, acc, i0, i1, wave, lane);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = 0.f;
-        }
-        if (!last && nxt.pi != cur.pi) S = stream_of(pb, nxt.pi);
-        cur = nxt;
-        ++idx;
-    };
-    const std::true_type REQ{};
-    const std::false_type NOREQ{};
-    const std::integral_constant<int, 0> H0{};
-    const std::integral_constant<int, 1> H1{};
-    while (true) {
-        if (idx + 2 < i1) step(REQ, H0);
-        else { step(NOREQ, H0); if (idx < i1) step(NOREQ, H1); break; }
-        if (idx + 2 < i1) step(REQ, H1);
-        else { step(NOREQ, H1); if (idx < i1) step(NOREQ, H0); break; }
-    }
-}
-
-// LDS of the streaming kernels: the digit window (bw = 3: SWR units, and the weight ring beside it)
-#define GOQ_GEMV_LDS                                                                                        \
-    constexpr bool RING = (BW == 3) && GOQ_RING3;                                                           \
-    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + (RING ? SWR : SW) * XG];                \
-    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];                                     \
-    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];                                    \
-    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256];                                 \
-    __shared__ __attribute__((aligned(1024))) unsigned char wring[RING ? WAVES * RING_SLOTS * 1024 : 1024]
+// LDS of the streaming kernels
+#define GOQ_GEMV_LDS                                                                     \
+    __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + SW * XG];            \
+    __shared__ __attribute__((aligned(16))) unsigned char stab[SW * 4];                  \
+    __shared__ __attribute__((aligned(256))) unsigned char vtab[64 * VS];                \
+    __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256]
 
 // Problems in the kernel arguments.  The leading scalar arguments repeat what the first
 // instructions of a workgroup need -- the piece sizes and the first unit of every problem -- as
@@ -885,10 +748,13 @@ void gemv_kernel(int pq, int pr, int bg1, int bg2, int bg3, int bg4, int bg5, in
         cur.rg = uniform((i0 - b0) / gn);
         cur.g = uniform((i0 - b0) % gn);
     }
-    const Problems<false> pb{a};
+    // `a` follows the nine leading ints (36 bytes) at the next 8-byte boundary of the segment
+    constexpr int KARG_P = 40 + (int)offsetof(GemvArgs, p);
+    const __attribute__((address_space(4))) char *kseg =
+        (const __attribute__((address_space(4))) char *)__builtin_amdgcn_kernarg_segment_ptr();
+    const Problems<false> pb{(const __attribute__((address_space(4))) GemvProblem *)(kseg + KARG_P), a.n};
     const Pieces pc{pq, pr, a.scratch};
-    if constexpr (RING) stream_piece_ring<ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx, wring);
-    else stream_piece<BW, ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
+    stream_piece<BW, ACT, false>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
 }
 
 // Problems in a table in device memory (goq_gemv_stream).
@@ -912,8 +778,7 @@ void gemv_stream_kernel(const GemvTable *__restrict__ T, Region *ws)
         cur.g = uniform(local % gn);
     }
     const Pieces pc{pq, pr, ws};
-    if constexpr (RING) stream_piece_ring<ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx, wring);
-    else stream_piece<BW, ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
+    stream_piece<BW, ACT, true>(pb, pc, i0, i1, cur, xtab, stab, vtab, cwx);
 }
 
 // Zero-fill of a caller-owned workspace (a kernel, not a memset node, so that a caller may
@@ -951,7 +816,7 @@ void gemv_rows_kernel(GemvArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char xtab[XZ + RW * XG];
     __shared__ __attribute__((aligned(16))) unsigned char stab[RW * 4];
-    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * 64];
+    __shared__ __attribute__((aligned(16))) unsigned char vtab[64 * VS];
     __shared__ __attribute__((aligned(16))) unsigned char cwx[WAVES * 256];
     __shared__ float red[NT];
     constexpr int CH = (BW == 3) ? 4 : 5;
@@ -988,7 +853,7 @@ void gemv_rows_kernel(GemvArgs a)
     Slice cur[RS], nxt[RS];
     request(0, cur);
 
-    for (int t = tid; t < 256; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t >> 2);
+    for (int t = tid; t < 64 * VC; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t / VC);
     if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
 
     // A operand of this lane, as in the kernel above
@@ -996,7 +861,7 @@ void gemv_rows_kernel(GemvArgs a)
     const int digit = 2 * (c >> 2) + (c & 1);
     const uint32_t abase = arow_live ? (uint32_t)(XZ + q * 256 + digit * 32) : 0u;
     const uint32_t amask = arow_live ? ~0u : 0u;
-    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane & 3) * 16;
+    const uint32_t vt_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)vtab + (lane % VC) * 16;
     unsigned char *cw = cwx + wave * 256;
 
     float acc = 0.f;
