@@ -286,6 +286,26 @@ def bench_gemv(args, shapes, bw, name):
     return res
 
 
+def mfma_peak_measured(goq, torch, kind, stream):
+    """goq_mfma_rate_probe: a loop of nothing but the matrix instruction (kind 0: f16 32x32x16, 1: i8
+    32x32x32), four independent accumulators per wavefront, 4 wavefronts per SIMD on every CU."""
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    iters, wgs = 4096, 256 * 4
+    goq.mfma_rate_probe(kind, wgs, 256, sink, stream=stream)
+    torch.cuda.synchronize()
+    best = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        ops = goq.mfma_rate_probe(kind, wgs, iters, sink, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        best = max(best, ops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return {"value": round(best, 1), "unit": "TFLOP/s" if kind == 0 else "TOP/s",
+            "what": "goq_mfma_rate_probe: %s only, %d workgroups x 4 wavefronts x %d x 4 instructions, best of 3"
+                    % ("v_mfma_f32_32x32x16_f16" if kind == 0 else "v_mfma_i32_32x32x32_i8", wgs, iters)}
+
+
 def gemv_kernel_name(bw, shapes):
     """The kernel the library launches for these layers in one goq_gemv_batch call (goq_gemv_plan)."""
     import paper_2605_26092_amd as goq
@@ -345,20 +365,23 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, 
     f16_path = act == goq.A16 or bw == 4
     peak = MFMA_F16_PEAK_TFLOPS if f16_path else MFMA_I8_PEAK_TOPS
     tops = issued / (ms * 1e-3) / 1e12
+    measured = mfma_peak_measured(goq, torch, 0 if f16_path else 1, stream)
     # HBM traffic per launch (mean over the block's matrices) from the committed counter runs, if
     # they cover this workload: the 7B block at 2048 tokens, W3/A16
-    traffic = None
+    traffic, traffic_source = None, None
     if bw == 3 and act == goq.A16 and tokens == 2048 and not folded and len(shapes) == 7 and shapes[0][1] == 4096:
         try:
             with open(os.path.join(ROOT, "profiles", "traffic.json.txt")) as fh:
-                traffic = json.load(fh)["gemm_kernel<3,0,false>"]["hbm_bytes_per_launch"]
+                t = json.load(fh)["gemm_kernel<3,0,false>"]
+                traffic, traffic_source = t["hbm_bytes_per_launch"], t.get("source")
         except (OSError, KeyError, ValueError):
             pass
     return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, {goq.A16: "A16", goq.A8: "A8", goq.A4: "A4"}[act]),
             "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1),
             "dense_equiv_TOPS": round(tops if folded else tops / 2, 1),
             "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if f16_path else "TOP/s",
-                         "frac": round(tops / peak, 4), "traffic": traffic}}
+                         "frac": round(tops / peak, 4), "traffic": traffic, "traffic_source": traffic_source,
+                         "peak_measured": measured}}
 
 
 def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
@@ -369,16 +392,7 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     act = {"A16": goq.A16, "A8": goq.A8, "A4": goq.A4}[act_name]
-    packed, canon = [], []
-    for idx, (_, out, inn) in enumerate(shapes):
-        q = goq_inputs.canonical_random(bw, out, inn, config_id=3, tensor_id=300 + idx)
-        canon.append(q)
-        pk = torch.empty(goq.packed_bytes(bw, out, inn), dtype=torch.uint8, device=dev)
-        d = [torch.from_numpy(q[k].view(np.int16) if q[k].dtype == np.uint16 else q[k]).to(dev)
-             for k in ("codes", "pattern", "signs", "c1", "c2")]
-        goq.pack(bw, out, inn, *d, pk)
-        torch.cuda.synchronize()
-        packed.append(pk)
+    packed, host_w = quantize_block_on_device(goq, torch, shapes, bw, 3, dev)
     g = bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=max(3, min(args.steps, 20)), warmup=2,
                          folded=folded)
     res = {
@@ -388,19 +402,22 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
         "dtype": "f16" if (act_name == "A16" or bw == 4) else "i8", "data": "synthetic",
         "config": {"workload": name, "bw": bw, "act": act_name, "group": 128, "tokens": tokens, "matrices": len(shapes),
                    "issued_ops_per_step": (2.0 if folded else 4.0) * tokens * sum(o * i for _, o, i in shapes),
-                   "dense_equiv_TOPS": g["dense_equiv_TOPS"]},
+                   "dense_equiv_TOPS": g["dense_equiv_TOPS"],
+                   "weights_from": "seeded fp16 weights quantised by goq_quantize (GEO mode) on the device",
+                   "clock": "HIP events on the launch stream around the timed launches"},
         "roofline": g["roofline"],
     }
-    res["cpu_baseline"] = None if args.no_cpu else cpu_baseline_gemm(canon, shapes, bw, act_name, tokens)
+    res["cpu_baseline"] = None if args.no_cpu else cpu_baseline_gemm(host_w[0], shapes, bw, act_name, tokens)
     return res
 
 
 def bench_quantize(args, shapes, bw, name):
     """The GEO quantizer on the device (goq_quantize): a step quantizes every matrix of the block.
-    Not the headline metric: reported in weights/s.  It is bound by fp64 vector arithmetic (one
-    lane per macro-block, sequential sums), so the roofline is the fp64 vector peak against the
-    method's fp64 operations per weight; its HBM traffic (2 B read + 1 B codes + 0.25 B metadata +
-    4/128 B coefficients written per weight) is reported under config."""
+    Not the headline metric: reported in weights/s.  It is bound by vector arithmetic (one
+    wavefront per macro-block; the sums of the method are carried out as exact 64-bit integer
+    sums, the residual, cross terms and scores in fp64), so the roofline is the fp64 vector peak
+    against the method's real-arithmetic operations per weight; its HBM traffic (2 B read + 1 B
+    codes + 0.25 B metadata + 4/128 B coefficients written per weight) is reported under config."""
     import torch
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")
@@ -480,16 +497,23 @@ def bench_ref(args, shapes, bw, tokens, name):
     torch.cuda.set_device(dev)
     bufs, flops = [], 0.0
     for idx, (_, out, inn) in enumerate(shapes):
-        q = goq_inputs.canonical_random(bw, out, inn, config_id=7, tensor_id=300 + idx)
         w = goq_inputs.weights(out, inn, config_id=7, tensor_id=idx)
         x = goq_inputs.activations_a16(tokens, inn, config_id=7, tensor_id=100 + idx, outlier_frac=0.01)
         gn = inn // 128
-        bufs.append((out, inn, torch.from_numpy(w.view(np.int16)).to(dev), torch.from_numpy(q["codes"]).to(dev),
-                     torch.from_numpy(q["pattern"]).to(dev), torch.from_numpy(q["signs"]).to(dev),
+        wd = torch.from_numpy(w.view(np.int16)).to(dev)
+        # bases from the GEO quantizer on the device (its coefficients are what REF mode replaces)
+        codes = torch.empty((out, inn), dtype=torch.uint8, device=dev)
+        pat = torch.empty((out, inn // 8), dtype=torch.uint8, device=dev)
+        sg = torch.empty((out, inn // 8), dtype=torch.uint8, device=dev)
+        g1 = torch.empty((out, gn), dtype=torch.int16, device=dev)
+        g2 = torch.empty((out, gn), dtype=torch.int16, device=dev)
+        goq.quantize(bw, out, inn, wd, codes, pat, sg, g1, g2)
+        torch.cuda.synchronize()
+        bufs.append((out, inn, wd, codes, pat, sg,
                      torch.from_numpy(x.view(np.int16)).to(dev),
                      torch.empty(goq.ref_workspace_bytes(inn), dtype=torch.uint8, device=dev),
                      torch.empty((out, gn), dtype=torch.int16, device=dev),
-                     torch.empty((out, gn), dtype=torch.int16, device=dev), (q, w, x)))
+                     torch.empty((out, gn), dtype=torch.int16, device=dev), (w, x)))
         flops += 2.0 * tokens * 128 * inn + out * gn * (4.0 * 128 * 128 + 10 * 128)
     stream = torch.cuda.current_stream()
     steps, warmup = max(3, min(args.steps, 20)), 2
@@ -525,9 +549,9 @@ def bench_ref(args, shapes, bw, tokens, name):
     else:
         from oracle import goq_oracle as O
         threads = min(O.max_threads(), os.cpu_count() or 1)
-        q, w, x = bufs[0][10]
+        w, x = bufs[0][10]
         rows, tk = 64, 64
-        qs = {k: (v[:rows] if isinstance(v, np.ndarray) else v) for k, v in q.items()}
+        qs = O.quantize_geo(bw, w[:rows], threads=threads)       # the oracle's own bases, untimed
         reps, t0 = 0, time.perf_counter()
         while True:
             O.ref_coefficients(qs, w[:rows], x[:tk], lam=1e-4, threads=threads)
@@ -543,11 +567,13 @@ def bench_ref(args, shapes, bw, tokens, name):
     return res
 
 
-def cpu_baseline_gemm(canon, shapes, bw, act_name, tokens):
-    """The oracle on a token slab of the first matrix (all outputs), issued-op rate."""
+def cpu_baseline_gemm(w0, shapes, bw, act_name, tokens):
+    """The oracle on a token slab of the first matrix (all outputs; the matrix quantised by the
+    oracle's own GEO quantizer first, untimed), issued-op rate."""
     from oracle import goq_oracle as O
     threads = min(O.max_threads(), os.cpu_count() or 1)
     _, out, inn = shapes[0]
+    canon = [O.quantize_geo(bw, w0, threads=threads)]
     slab = 32 if act_name == "A16" else 64
     if act_name == "A16":
         x = goq_inputs.activations_a16(slab, inn, config_id=3, tensor_id=100, outlier_frac=0.01)
