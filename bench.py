@@ -620,7 +620,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2048)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=192)
     ap.add_argument("--settle-ms", type=float, default=300.0,
                     help="GEMV workloads: milliseconds of untimed launches before the warm-up that let the GPU clocks settle")
     ap.add_argument("--stream-blocks", type=int, default=0,

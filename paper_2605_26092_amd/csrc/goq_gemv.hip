@@ -80,6 +80,9 @@ constexpr int XZ = 256;                  // zero bytes in front of the digit tab
 #ifndef GOQ_CB
 #define GOQ_CB 16
 #endif
+#ifndef GOQ_SCHED_GROUPS
+#define GOQ_SCHED_GROUPS 1
+#endif
 #ifndef GOQ_VCOPIES
 #define GOQ_VCOPIES 16
 #endif
@@ -439,20 +442,34 @@ __device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t md, u
     // primary codes are decoded (bw = 4 has fewer registers to spare)
     constexpr int LA = (BW == 3) ? 4 : 2;
     u32x4 ev[4];
-    auto request = [&](int k) {
-        uint32_t eo;                       // LDS address of the entry: vt + VS * (pattern | signs << 2)
+    auto address = [&](int k) {            // LDS address of the entry: vt + VS * (pattern | signs << 2)
         if constexpr (BW == 3) {
             // a_0 (bits 6..7), a_1 (14..15), a_2 (22..23) are the top two bits of bytes 0..2: a
             // byte dot product with weights 1, 4, 16 gives 64 (a_0 + 4 a_1 + 16 a_2); the weights
             // are scaled to the entry stride VS
-            eo = __builtin_amdgcn_udot4(dw[k] & 0x00C0C0C0u, 0x00100401u * (VS / 64), vt, false);
+            return __builtin_amdgcn_udot4(dw[k] & 0x00C0C0C0u, 0x00100401u * (VS / 64), vt, false);
         } else {
-            eo = vt + ((md >> (6 * k)) & 63u) * VS;
+            return vt + ((md >> (6 * k)) & 63u) * VS;
         }
+    };
+    auto fetch = [&](int k, uint32_t eo) {
         ev[k] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(eo);
     };
+    auto request = [&](int k) { fetch(k, address(k)); };
+    {
+        // the addresses first, then the reads: a dot-product result needs a few cycles before an
+        // LDS instruction may use it as address, which the other address computations cover
+        uint32_t eo[LA];
 #pragma unroll
-    for (int k = 0; k < LA; ++k) request(k);
+        for (int k = 0; k < LA; ++k) eo[k] = address(k);
+#if GOQ_SCHED_GROUPS
+#pragma unroll
+        for (int k = 0; k < LA; ++k) __builtin_amdgcn_sched_group_barrier(0x002, BW == 3 ? 2 : 3, 0);   // VALU
+        __builtin_amdgcn_sched_group_barrier(0x100, LA, 0);                                            // DS read
+#endif
+#pragma unroll
+        for (int k = 0; k < LA; ++k) fetch(k, eo[k]);
+    }
     v8i B1, B2;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
