@@ -94,3 +94,79 @@ def test_gemv_plan_follows_the_documented_choice(goq):
         goq.gemv_select(goq.GEMV_AUTO)
     with pytest.raises(goq.GoqError):
         goq.gemv_plan(3, goq.A16, [(64, 100)])
+
+
+def _table_words(goq, bw, act, shapes):
+    """goq_gemv_stream_table on descriptors with made-up (aligned, never dereferenced) pointers ->
+    (header int32 view, problems as int32 rows of 16)."""
+    import numpy as np
+    from paper_2605_26092_amd import binding as b
+    arr = (b._Desc * len(shapes))()
+    for i, (d, (out, inn)) in enumerate(zip(arr, shapes)):
+        d.out, d.in_ = out, inn
+        d.packed, d.x, d.y = 0x100000 * (i + 1), 0x100000 * (i + 1) + 0x1000, 0x100000 * (i + 1) + 0x2000
+        d.sx = None if act == goq.A16 else 0x100000 * (i + 1) + 0x3000
+        d.ytype = goq.F32
+    th, nbytes = goq.gemv_stream_table(bw, act, arr)
+    raw = np.frombuffer((ctypes.c_ubyte * nbytes).from_address(ctypes.addressof(th)), dtype=np.uint8).copy()
+    words = raw.view(np.int32)
+    nprob = words[3]
+    return words, words[len(words) - 16 * nprob:].reshape(nprob, 16)
+
+
+def test_stream_table_cuts_the_unit_sequence_into_pieces(goq):
+    """Host logic of goq_gemv_stream_table: units = row groups (512 rows) x macro-blocks of all
+    problems in order; min(units, 512) pieces whose sizes differ by at most one, the larger first;
+    first[b] = the problem that holds the first unit of piece b."""
+    block = [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)]
+    for shapes in ([(100, 256)], block, block * 32, [(1, 128), (700, 512), (64, 4096), (3000, 128)] * 5):
+        words, probs = _table_words(goq, 3, goq.A16, shapes)
+        magic, bw, act, n, total, nwg, pq, pr = (int(v) for v in words[:8])
+        assert magic == 0x51544247 and bw == 3 and act == goq.A16 and n == len(shapes)
+        units = [((out + 511) // 512) * (inn // 128) for out, inn in shapes]
+        begins = [sum(units[:i]) for i in range(n)]
+        assert total == sum(units) and nwg == min(total, 512)
+        assert (pq, pr) == (total // nwg, total % nwg)
+        # problem fields: gn at dword 9, rbn 11, rgroups 12, begin 13 (after four pointers and `out`)
+        for i, (out, inn) in enumerate(shapes):
+            assert int(probs[i][8]) == out and int(probs[i][9]) == inn // 128
+            assert int(probs[i][11]) == (out + 63) // 64 and int(probs[i][12]) == (out + 511) // 512
+            assert int(probs[i][13]) == begins[i]
+        first = words[16:16 + 512]
+        for piece in range(nwg):
+            i0 = piece * pq + min(piece, pr)
+            holder = max(i for i in range(n) if begins[i] <= i0)
+            assert int(first[piece]) == holder, (piece, i0)
+
+
+def test_stream_entry_points_reject_bad_arguments_on_the_host(goq):
+    from paper_2605_26092_amd import binding as b
+    L = goq.lib()
+    n = ctypes.c_size_t()
+    assert L.goq_gemv_stream_table_bytes(0, ctypes.byref(n)) == b.ESHAPE
+    assert L.goq_gemv_stream_table_bytes(65537, ctypes.byref(n)) == b.ESHAPE
+    assert L.goq_gemv_stream_table_bytes(7, None) == b.EINVAL
+    assert L.goq_gemv_stream_table_bytes(224, ctypes.byref(n)) == b.OK and n.value == 2112 + 224 * 64
+    arr = (b._Desc * 1)()
+    arr[0].out, arr[0].in_, arr[0].packed, arr[0].x, arr[0].y, arr[0].ytype = 64, 128, 0x1000, 0x2000, 0x3000, goq.F32
+    buf = (ctypes.c_uint64 * 512)()
+    assert L.goq_gemv_stream_table(3, goq.A16, 1, arr, None) == b.EINVAL
+    assert L.goq_gemv_stream_table(3, goq.A16, 1, arr, ctypes.addressof(buf) + 4) == b.EINVAL
+    assert L.goq_gemv_stream_table(3, goq.A16, 0, arr, ctypes.addressof(buf)) == b.ESHAPE
+    assert L.goq_gemv_stream_table(5, goq.A16, 1, arr, ctypes.addressof(buf)) == b.EINVAL
+    assert L.goq_gemv_stream_table(3, goq.A8, 1, arr, ctypes.addressof(buf)) == b.EINVAL       # A8 needs sx
+    arr[0].in_ = 100
+    assert L.goq_gemv_stream_table(3, goq.A16, 1, arr, ctypes.addressof(buf)) == b.ESHAPE
+    arr[0].in_ = 128
+    assert L.goq_gemv_stream_table(3, goq.A16, 1, arr, ctypes.addressof(buf)) == b.OK
+    fake = 0x10000
+    # a host table that goq_gemv_stream_table did not write is refused before any launch
+    junk = (ctypes.c_uint64 * 512)()
+    assert L.goq_gemv_stream(None, ctypes.addressof(junk), fake, fake) == b.EINVAL
+    assert L.goq_gemv_stream(None, None, fake, fake) == b.EINVAL
+    assert L.goq_gemv_stream(None, ctypes.addressof(buf), fake + 8, fake) == b.EINVAL           # table_dev misaligned
+    assert L.goq_gemv_stream(None, ctypes.addressof(buf), fake, fake + 16) == b.EINVAL          # workspace misaligned
+    assert L.goq_gemv_workspace_bytes(None) == b.EINVAL
+    assert L.goq_gemv_workspace_bytes(ctypes.byref(n)) == b.OK and n.value > 2 * 512 * 512 * 4
+    assert L.goq_gemv_batch_ws(None, 3, goq.A16, 1, arr, None) == b.EINVAL
+    assert L.goq_gemv_batch_ws(None, 3, goq.A16, 1, arr, fake + 16) == b.EINVAL
