@@ -210,3 +210,52 @@ def test_config2_stream_of_32_blocks_full_size(oracle):
         worst = max(worst, e1)
         assert e1 <= TOL, (k // 7, goq_inputs.LLAMA2_7B_BLOCK[k % 7][0], e1)
     print("config2 stream: worst relative error %.3g" % worst, flush=True)
+
+
+@pytest.mark.parametrize("bw,act_name", [(3, "A16"), (4, "A8")])
+def test_stream_of_thousands_of_tiny_problems(oracle, bw, act_name):
+    """3000 problems of one to three units each (five small layers reused with activations of their
+    own): every piece of the launch spans several problems, windows of staged activations cross
+    many problem boundaries, most row groups end inside a window."""
+    import paper_2605_26092_amd as goq
+    torch = gu.torch_cuda()
+    layers = [(1, 128), (64, 128), (70, 256), (130, 128), (33, 384)]
+    base = []
+    for i, (out, inn) in enumerate(layers):
+        q = oracle.quantize_geo(bw, goq_inputs.weights(out, inn, config_id=64, tensor_id=i), threads=8)
+        base.append((q, gu.pack_layer(goq, q)))
+    rng = np.random.default_rng(640 + bw)
+    nprob = 3000
+    pick = rng.integers(0, len(layers), nprob)
+    probs, ys, refs, keep = [], [], [], []
+    for k in range(nprob):
+        q, packed = base[pick[k]]
+        out, inn = layers[pick[k]]
+        if act_name == "A16":
+            x = goq_inputs.activations_a16(1, inn, config_id=64, tensor_id=1000 + k, outlier_frac=0.01)
+            refs.append(oracle.gemm_a16(q, x, threads=1)[0])
+            xd, sxd = gu.to_dev(x.reshape(-1)), None
+        else:
+            xq, sx = goq_inputs.activations_int(1, inn, 8, config_id=64, tensor_id=1000 + k)
+            refs.append(oracle.gemm_a8(q, xq, sx, threads=1)[0][0])
+            xd, sxd = gu.to_dev(xq.reshape(-1)), gu.to_dev(sx)
+        y = torch.full((out,), float("nan"), dtype=torch.float32, device="cuda")
+        keep += [xd, sxd]
+        ys.append(y)
+        probs.append((out, inn, packed, xd, sxd, y, goq.F32))
+    print("tiny-problem stream: %d problems, bw=%d %s" % (nprob, bw, act_name), flush=True)
+    ws = _workspace(goq)
+    th, nbytes = goq.gemv_stream_table(bw, getattr(goq, act_name), probs)
+    td = _table_to_device(th, nbytes)
+    for rep in range(2):
+        goq.gemv_stream(th, td, ws)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for k in range(nprob):
+        yn = ys[k].cpu().numpy().astype(np.float64)
+        assert not np.isnan(yn).any(), k
+        ref = refs[k]
+        e = float(np.max(np.abs(yn - ref) / np.maximum(np.abs(ref), 1e-2 * np.sqrt(np.mean(ref ** 2)) + 1e-30)))
+        worst = max(worst, e)
+        assert e <= TOL, (k, layers[pick[k]], e)
+    print("tiny-problem stream: worst relative error %.3g" % worst, flush=True)
