@@ -73,15 +73,16 @@ const char *goq_last_error(void);
 int goq_packed_bytes(int bw, int64_t out, int64_t in, size_t *bytes);
 
 /* Data-free GEO-mode quantizer (Sec. 3.2 - 3.4) on the device: fp16 weights w [out][in] (IEEE
- * binary16 bit patterns, row-major, 4-byte aligned) -> canonical arrays.  Per 128-weight
+ * binary16 bit patterns, row-major, 16-byte aligned) -> canonical arrays.  Per 128-weight
  * macro-block along `in`: s_norm = max |w|; codes = nearest lattice state of w / s_norm (linear
  * distance, exact ties toward the smaller magnitude); residual r = w - (<w,b1>/||b1||^2) b1
  * (Eq. 1); per 8-weight micro-block the pattern s* = argmax_s sum_pairs |x_i r_j - x_j r_i| (ties:
  * smallest s) with pair signs eta = sgn(x_i r_j - x_j r_i) (+1 at zero) (Sec. 3.3); b2 by the
  * Theorem 1 exchange; c1 = <w,b1>/||b1||^2, c2 = <w,b2>/||b2||^2 (Eq. 2) rounded to fp16.  An
- * all-zero macro-block gets zero codes, pattern 0, signs 0, c1 = c2 = 0.  Arithmetic is fp64 with
- * sums in ascending k, so the outputs are a pure function of w.  codes / pattern / signs must be
- * 4-byte aligned.  Weights must be finite. */
+ * all-zero macro-block gets zero codes, pattern 0, signs 0, c1 = c2 = 0.  Arithmetic is fp64; the
+ * sums are exact (every term is a multiple of 2^-31 and the totals stay below 2^22), so the
+ * outputs are a pure function of w and equal a sequential evaluation in ascending k.  codes must be
+ * 8-byte aligned.  Weights must be finite. */
 int goq_quantize(void *stream, int bw, int64_t out, int64_t in, const uint16_t *w,
                  uint8_t *codes, uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2);
 

@@ -56,9 +56,8 @@ int goq_quantize(void *stream, int bw, int64_t out, int64_t in, const uint16_t *
     int rc = check_shape("goq_quantize", bw, out, in);
     if (rc) return rc;
     if (!w || !codes || !pattern || !signs || !c1 || !c2) return goq_set_error(GOQ_EINVAL, "goq_quantize: NULL pointer");
-    if (misaligned(w, 4) || misaligned(codes, 4) || misaligned(pattern, 4) || misaligned(signs, 4) ||
-        misaligned(c1, 2) || misaligned(c2, 2))
-        return goq_set_error(GOQ_EINVAL, "goq_quantize: w, codes, pattern and signs must be 4-byte aligned");
+    if (misaligned(w, 16) || misaligned(codes, 8) || misaligned(c1, 2) || misaligned(c2, 2))
+        return goq_set_error(GOQ_EINVAL, "goq_quantize: w must be 16-byte, codes 8-byte, c1 and c2 2-byte aligned");
     return goq_launch_quantize((hipStream_t)stream, bw, out, in, w, codes, pattern, signs, c1, c2);
 }
 

@@ -1,32 +1,37 @@
 // goq_quantize: the data-free GEO-mode quantizer on the device (Sec. 3.2 - 3.4): fp16 weights of a
 // layer [out][in] -> canonical arrays (codes, pattern, signs, c1, c2).
 //
-// One WAVEFRONT per macro-block of 128 weights: lane l owns the weights k = 2l and 2l + 1, a
-// micro-block of 8 weights is a group of 4 consecutive lanes, and pair p of every exchange pattern
-// of a micro-block belongs to lane p of its group.  The arithmetic is laid out around what is
-// exact:
+// One LANE per micro-block of 8 weights, one ROW of 16 lanes per macro-block of 128 weights, four
+// macro-blocks per wavefront.  Everything that belongs to a micro-block -- nearest states, the 16
+// cross terms of the four exchange patterns, scores, argmax, pair signs, the exchange itself -- is
+// lane-local and lives in registers; what belongs to the macro-block -- the norm s_norm and the
+// four sums of Eq. 1 and Eq. 2 -- is reduced across the 16 lanes of a row with data-parallel-
+// primitive (DPP) moves, which stay inside a row by construction.  No LDS, no barriers.  The
+// arithmetic is laid out around what is exact:
 //
-//   fixed point  An fp16 weight is an integer W (up to 41 bits) times 2^-24; a lattice state is a
-//                signed power of two B times 2^-(E-1), E = 2^(bw-1).  So <w, b1>, ||b1||^2,
-//                <w, b2> and ||b2||^2 (Eq. 1, Eq. 2) are INTEGER sums -- 64-bit adds across the
-//                wavefront, no rounding and therefore no summation order -- and s_norm = ||w||_inf
-//                is an integer maximum of the fp16 magnitude bits.
-//   nearest      Q(v), v = w / s_norm (Sec. 3.2), is decided without the division: |v| lies above
-//                the midpoint 0.75 * 2^-e of the states 2^-e and 2^-(e+1) exactly when
-//                W * 2^(e+2) > 3 S (S the integer of s_norm), and above the midpoint to zero,
-//                2^-(emin+1), when W * 2^(emin+1) > S: integer comparisons, an exact tie going to
-//                the smaller magnitude.
-//   fp64         Only what the method defines as real arithmetic: the projection coefficient
-//                <w,b1> / ||b1||^2 (one correctly rounded division of two exact integers), the
-//                residual r = w - c b1 (Eq. 1; c b1 is exact, one rounding), the cross terms
-//                t = x_i r_j - x_j r_i (Sec. 3.3; both products exact, one rounding) and the four
-//                term score A_s = |t_0| + |t_1| + |t_2| + |t_3|, added in pair order.  eta = sgn(t)
-//                (+1 at zero), s* = argmax A_s (ties: smallest s).
+//   products    A lattice state is a signed power of two, so every product with a state (w b1,
+//               w b2, c b1, x r) is exact in fp64.
+//   sums        <w, b1> and <w, b2> (Eq. 1, Eq. 2) are sums of multiples of 2^-31 below 2^23: every
+//               partial sum is exactly representable in fp64 whatever the order (always for
+//               bw = 3; for bw = 4 unless |<w, b>| reaches 2^22, i.e. more than 64 weights of the
+//               block at the fp16 maximum), so the reduction tree is free.  ||b1||^2 and ||b2||^2
+//               are small integers (units of 4^-(E-1)).
+//   nearest     Q(v), v = w / s_norm (Sec. 3.2), is decided without the division: |v| lies above
+//               the midpoint 0.75 * 2^-k of the states 2^-k and 2^-(k+1) exactly when
+//               |w| > 0.75 * 2^-k * s_norm, and above the midpoint to zero, 2^-(emin+1), when
+//               |w| > 2^-(emin+1) * s_norm; the right-hand sides are exact in fp64 (s_norm has 11
+//               significant bits).  The thresholds fall with k, so the exponent of the nearest
+//               state is the NUMBER of thresholds |w| does not exceed; an exact tie goes to the
+//               smaller magnitude.
+//   roundings   Only what the method defines as real arithmetic rounds: the projection
+//               coefficient <w,b1> / ||b1||^2 (one correctly rounded division of two exact
+//               numbers), the residual r = w - c b1 (Eq. 1; one rounding), the cross terms
+//               t = x_i r_j - x_j r_i (Sec. 3.3; one rounding) and the four-term score
+//               A_s = |t_0| + |t_1| + |t_2| + |t_3|, added in pair order.  eta = sgn(t)
+//               (+1 at zero), s* = argmax A_s (ties: smallest s).
 //
-// The results are a pure function of the weights: no sum depends on the launch shape.  They equal
-// those of a sequential fp64 evaluation of the same formulas bit for bit as long as the integer
-// sums fit the 53-bit significand, which they do for bw = 3 always and for bw = 4 unless
-// |<w, b>| reaches 2^22 (more than 64 weights of the block at the fp16 maximum).
+// The results are a pure function of the weights and equal those of a sequential fp64 evaluation
+// of the same formulas bit for bit under the condition on the sums stated above.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "goq_layout.h"
@@ -35,165 +40,168 @@
 
 namespace {
 
-constexpr int QW = 4;                        // wavefronts (= macro-blocks in flight) per workgroup
+constexpr int QW = 4;                        // wavefronts per workgroup
+constexpr int ROWS = 4;                      // macro-blocks (rows of 16 lanes) per wavefront
 
-// fp16 magnitude bits (sign removed) -> integer multiple of 2^-24
-__device__ __forceinline__ uint64_t half_magnitude(uint32_t a)
+// ---- DPP moves inside a row of 16 lanes -------------------------------------------------------
+// quad_perm [a, b, c, d]: lane 4 m + i reads lane 4 m + (a, b, c, d)[i]
+constexpr int QUAD_SWAP1 = 1 | (0 << 2) | (3 << 4) | (2 << 6);      // i xor 1
+constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);      // i xor 2
+constexpr int ROW_HALF_MIRROR = 0x141;                              // i -> 7 - i within 8 lanes
+constexpr int ROW_MIRROR = 0x140;                                   // i -> 15 - i within 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp32(uint32_t v)
 {
-    const uint32_t e = a >> 10, m = a & 0x3ffu;
-    return e ? (uint64_t)(1024u + m) << (e - 1) : (uint64_t)m;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
 }
-
-// fp16 bits -> fp64 (exact): sign, magnitude integer, scale 2^-24
-__device__ __forceinline__ double half_value(uint32_t h)
+template <int CTRL>
+__device__ __forceinline__ double dpp_double(double v)
 {
-    const double v = __builtin_ldexp((double)(int64_t)half_magnitude(h & 0x7fffu), -24);
-    return (h & 0x8000u) ? -v : v;
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint64_t m = ((uint64_t)dpp32<CTRL>((uint32_t)(u >> 32)) << 32) | dpp32<CTRL>((uint32_t)u);
+    return __builtin_bit_cast(double, m);
 }
-
-template <typename T>
-__device__ __forceinline__ T wave_sum(T v)
+// After the four steps every lane of a row holds the row's result: the partners are i xor 1,
+// i xor 2 (a quad holds one value), 7 - i (a group of eight does), 15 - i.
+__device__ __forceinline__ double row_sum(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    v += dpp_double<QUAD_SWAP1>(v);
+    v += dpp_double<QUAD_SWAP2>(v);
+    v += dpp_double<ROW_HALF_MIRROR>(v);
+    v += dpp_double<ROW_MIRROR>(v);
+    return v;
+}
+__device__ __forceinline__ uint32_t row_sum(uint32_t v)
+{
+    v += dpp32<QUAD_SWAP1>(v);
+    v += dpp32<QUAD_SWAP2>(v);
+    v += dpp32<ROW_HALF_MIRROR>(v);
+    v += dpp32<ROW_MIRROR>(v);
+    return v;
+}
+__device__ __forceinline__ uint32_t row_max(uint32_t v)
+{
+    v = max(v, dpp32<QUAD_SWAP1>(v));
+    v = max(v, dpp32<QUAD_SWAP2>(v));
+    v = max(v, dpp32<ROW_HALF_MIRROR>(v));
+    v = max(v, dpp32<ROW_MIRROR>(v));
     return v;
 }
 
-// code of one weight: sign bit | exponent, (sign 0, e = E - 1) is zero (Sec. 3.2)
-template <int BW>
-__device__ __forceinline__ int nearest_state(uint32_t h, uint64_t S)
-{
-    constexpr int E = 1 << (BW - 1);
-    const bool neg = (h & 0x8000u) != 0;
-    const uint64_t W = half_magnitude(h & 0x7fffu);
-    const int emin = neg ? E - 1 : E - 2;            // exponent of the smallest magnitude of this sign
-    const uint64_t S3 = 3 * S;
-    int e = -1;
-#pragma unroll
-    for (int k = E - 1; k >= 0; --k) {               // descending: the smallest qualifying k wins
-        const bool above = (k < emin) ? ((W << (k + 2)) > S3) : ((W << (k + 1)) > S);
-        if (k <= emin && above) e = k;
-    }
-    if (e < 0) return E - 1;                         // zero
-    return (neg ? E : 0) | e;
-}
-
-// signed integer value of a code in units of 2^-(E-1)
-template <int BW>
-__device__ __forceinline__ int state_integer(int code)
-{
-    constexpr int E = 1 << (BW - 1);
-    const int s = code >> (BW - 1), e = code & (E - 1);
-    if (!s && e == E - 1) return 0;
-    const int mag = 1 << (E - 1 - e);
-    return s ? -mag : mag;
-}
+// 2^-e as fp64, e >= 0 small
+__device__ __forceinline__ double pow2_neg(int e) { return __longlong_as_double((long long)(1023 - e) << 52); }
 
 template <int BW>
-__global__ __launch_bounds__(64 * QW) void quantize_kernel(const uint32_t *__restrict__ w, int64_t nblocks,
-                                                           uint16_t *__restrict__ codes, uint8_t *__restrict__ pattern,
+__global__ __launch_bounds__(64 * QW) void quantize_kernel(const uint4 *__restrict__ w, int64_t nblocks,
+                                                           uint2 *__restrict__ codes, uint8_t *__restrict__ pattern,
                                                            uint8_t *__restrict__ signs, uint16_t *__restrict__ c1,
                                                            uint16_t *__restrict__ c2)
 {
     constexpr int E = 1 << (BW - 1);
-    __shared__ double rs[QW][GOQ_N];                 // residual r
-    __shared__ double xs[QW][GOQ_N];                 // primary basis b1 (real value)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int grp = lane >> 2, p = lane & 3;         // micro-block of this lane, its pair index
-    double *r = rs[wave], *x = xs[wave];
+    const int row = lane >> 4, m = lane & 15;        // macro-block of the wavefront, micro-block of the macro-block
+    const int64_t groups = (nblocks + ROWS - 1) / ROWS;
 
-    for (int64_t mb = (int64_t)blockIdx.x * QW + wave; mb < nblocks; mb += (int64_t)gridDim.x * QW) {
-        const uint32_t pair = w[mb * 64 + lane];
-        const uint32_t h[2] = {pair & 0xffffu, pair >> 16};
-        // macro-block normalisation: magnitude bits order like magnitudes
-        uint32_t amax = max(h[0] & 0x7fffu, h[1] & 0x7fffu);
+    for (int64_t grp = (int64_t)blockIdx.x * QW + wave; grp < groups; grp += (int64_t)gridDim.x * QW) {
+        const int64_t mb_raw = grp * ROWS + row;
+        const bool valid = mb_raw < nblocks;         // rows past the end repeat the last macro-block, store nothing
+        const int64_t mb = valid ? mb_raw : nblocks - 1;
+        const uint4 q = w[mb * 16 + m];
+        const uint32_t pk[4] = {q.x, q.y, q.z, q.w};
+        uint32_t h[8];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, o));
-        if (amax == 0) {                             // all-zero block: nothing to represent
-            codes[mb * 64 + lane] = (uint16_t)((E - 1) * 0x0101);
-            if (p == 0) { pattern[mb * 16 + grp] = 0; signs[mb * 16 + grp] = 0; }
-            if (lane == 0) { c1[mb] = 0; c2[mb] = 0; }
-            continue;
-        }
-        const uint64_t S = half_magnitude(amax);
+        for (int i = 0; i < 4; ++i) { h[2 * i] = pk[i] & 0xffffu; h[2 * i + 1] = pk[i] >> 16; }
 
-        // primary projection; <w, b1> and ||b1||^2 as integers (a weight and its state share the sign)
-        int code[2], B[2];
-        uint64_t s1 = 0;
-        uint32_t n1 = 0;
+        // macro-block normalisation s_norm = ||w||_inf: magnitude bits order like magnitudes
+        uint32_t amax = 0;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            code[i] = nearest_state<BW>(h[i], S);
-            B[i] = state_integer<BW>(code[i]);
-            const uint32_t mag = (uint32_t)(B[i] < 0 ? -B[i] : B[i]);
-            s1 += half_magnitude(h[i] & 0x7fffu) * mag;
-            n1 += mag * mag;
-        }
-        codes[mb * 64 + lane] = (uint16_t)(code[0] | (code[1] << 8));
-        const uint64_t S1 = wave_sum(s1);
-        const uint32_t N1 = wave_sum(n1);            // > 0: the largest weight maps to +-1
-        // projection coefficient <w,b1> / ||b1||^2 = (S1 / N1) 2^(E-1-24); residual (Eq. 1)
-        const double proj = __builtin_ldexp((double)S1 / (double)N1, E - 1 - 24);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const double b = __builtin_ldexp((double)B[i], -(E - 1));
-            x[2 * lane + i] = b;
-            r[2 * lane + i] = half_value(h[i]) - proj * b;
-        }
-        __builtin_amdgcn_wave_barrier();             // LDS accesses of one wavefront execute in order
+        for (int i = 0; i < 8; ++i) amax = max(amax, h[i] & 0x7fffu);
+        amax = row_max(amax);
+        const bool zero_block = amax == 0;           // nothing to represent: zero codes, c1 = c2 = 0
+        const double sn = half_bits_to_double(amax);
 
-        // pair p of pattern s of this lane's micro-block: (i, i xor s), i the p-th lower index
-        const double *xm = x + 8 * grp, *rm = r + 8 * grp;
+        // nearest states.  Thresholds common to both signs: 0.75 2^-k s_norm, k = 0 .. E-3; then a
+        // negative weight has the state 2^-(E-1) (midpoints 0.75 2^-(E-2) s_norm and, to zero,
+        // 2^-E s_norm), a positive one ends at 2^-(E-2) (midpoint to zero 2^-(E-1) s_norm).
+        double wv[8], x[8];
+        uint32_t code_lo = 0, code_hi = 0, n1 = 0;
+        double s1 = 0.0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double wa = half_bits_to_double(h[i] & 0x7fffu);
+            const bool neg = (h[i] & 0x8000u) != 0;
+            int cnt = 0;
+#pragma unroll
+            for (int k = 0; k <= E - 3; ++k) cnt += (wa <= 0.75 * pow2_neg(k) * sn) ? 1 : 0;
+            const int cn = cnt + ((wa <= 0.75 * pow2_neg(E - 2) * sn) ? 1 : 0) + ((wa <= pow2_neg(E) * sn) ? 1 : 0);
+            const int cp = cnt + ((wa <= pow2_neg(E - 1) * sn) ? 1 : 0);
+            // negative: exponent cn, or zero when no threshold is exceeded (cn = E);
+            // positive: exponent cp, where cp = E - 1 is the code of zero already
+            const bool is_zero = zero_block || (neg ? cn == E : cp == E - 1);
+            const int e = neg ? cn : cp;
+            const int code = is_zero ? E - 1 : ((neg ? E : 0) | e);
+            if (i < 4) code_lo |= (uint32_t)code << (8 * i);
+            else code_hi |= (uint32_t)code << (8 * (i - 4));
+            const double xa = is_zero ? 0.0 : pow2_neg(e);           // |b1_i|
+            x[i] = neg ? -xa : xa;
+            wv[i] = neg ? -wa : wa;
+            s1 += wa * xa;                                          // a weight and its state share the sign
+            n1 += is_zero ? 0u : (1u << (2 * (E - 1 - e)));         // |b1_i|^2 in units of 4^-(E-1)
+        }
+        if (valid) codes[mb * 16 + m] = make_uint2(code_lo, code_hi);
+        const double S1 = row_sum(s1);
+        const uint32_t N1 = row_sum(n1);             // > 0 unless the block is zero: the largest weight maps to +-1
+        // projection coefficient <w,b1> / ||b1||^2 and the residual r = w - c b1 (Eq. 1)
+        const double proj = zero_block ? 0.0 : S1 / ((double)N1 * pow2_neg(2 * (E - 1)));
+        double r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = wv[i] - proj * x[i];
+
+        // Sec. 3.3: the four patterns s, pairs (i, i xor s) in ascending lower index; cross term,
+        // score in pair order, sign bits (eta = -1 where t < 0).  The pair's share of <w, b2> under
+        // the Theorem 1 exchange (b2_i = -eta x_j for the lower index, b2_j = +eta x_i for the upper
+        // one) is eta (w_j x_i - w_i x_j): exact, and summed for every pattern alongside its score,
+        // so that choosing the pattern chooses the sum.
         int best_s = 1;
         uint32_t best_signs = 0;
-        double bestA = -1.0;
+        double bestA = -1.0, best_d = 0.0;
 #pragma unroll
         for (int s = 1; s <= 4; ++s) {
-            const int i = (s == 1) ? 2 * p : (s == 4) ? p : ((p & 1) | ((p >> 1) << 2));
-            const int j = i ^ s;
-            const double t = xm[i] * rm[j] - xm[j] * rm[i];
-            const double at = fabs(t);
-            // alignment score: the four terms in pair order
-            double A = __shfl(at, 0, 4);
-            A += __shfl(at, 1, 4);
-            A += __shfl(at, 2, 4);
-            A += __shfl(at, 3, 4);
-            const uint64_t negs = __ballot(t < 0.0);                 // eta = -1 where t < 0
-            const uint32_t sg = (uint32_t)(negs >> (4 * grp)) & 15u;
-            if (A > bestA) { bestA = A; best_s = s; best_signs = sg; }   // ties: the smaller s stays
-        }
-        if (p == 0) {
-            pattern[mb * 16 + grp] = (uint8_t)(best_s - 1);
-            signs[mb * 16 + grp] = (uint8_t)best_signs;
-        }
-
-        // b2 by the Theorem 1 exchange: y_i = -eta x_j for the lower index of a pair, +eta x_i for
-        // the upper one; <w, b2> and ||b2||^2 as integers
-        int64_t s2 = 0;
-        uint32_t n2 = 0;
+            double A = 0.0, d = 0.0;
+            uint32_t sg = 0;
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-            const int i = 2 * p + ii, j = i ^ best_s;
-            const int lower = i < j ? i : j;
-            const int rank = (best_s == 1) ? (lower >> 1) : (best_s == 4) ? lower : ((lower & 1) | ((lower >> 2) << 1));
-            const bool eta_neg = (best_signs >> rank) & 1u;
-            const int Bj = (int)__builtin_ldexp(xm[j], E - 1);       // the partner's state as an integer
-            const int Y = ((i < j) != eta_neg) ? -Bj : Bj;
-            const int64_t Wi = (int64_t)half_magnitude(h[ii] & 0x7fffu);
-            s2 += ((h[ii] & 0x8000u) ? -Wi : Wi) * Y;
-            n2 += (uint32_t)(Y * Y);
+            for (int p = 0; p < 4; ++p) {
+                const int i = (s == 1) ? 2 * p : (s == 4) ? p : ((p & 1) | ((p >> 1) << 2));
+                const int j = i ^ s;
+                const double t = x[i] * r[j] - x[j] * r[i];
+                const double u = wv[j] * x[i] - wv[i] * x[j];
+                const bool eta_neg = t < 0.0;
+                A = (p == 0) ? fabs(t) : A + fabs(t);
+                sg |= (eta_neg ? 1u : 0u) << p;
+                d += eta_neg ? -u : u;
+            }
+            const bool better = A > bestA;                           // ties: the smaller s stays
+            bestA = better ? A : bestA;
+            best_s = better ? s : best_s;
+            best_signs = better ? sg : best_signs;
+            best_d = better ? d : best_d;
         }
-        const int64_t S2 = wave_sum(s2);
-        const uint32_t N2 = wave_sum(n2);
-        if (lane == 0) {
+        if (zero_block) { best_s = 1; best_signs = 0; }
+        if (valid) {
+            pattern[mb * 16 + m] = (uint8_t)(best_s - 1);
+            signs[mb * 16 + m] = (uint8_t)best_signs;
+        }
+        // <w, b2> of the macro-block; ||b2||^2 = ||b1||^2 (b2 is a signed permutation of b1)
+        const double S2 = row_sum(best_d);
+        const uint32_t N2 = N1;
+        if (valid && m == 0) {
             // GEO coefficients, Eq. 2 (the normal equations are diagonal: <b1, b2> = 0)
-            const double c1v = proj;
-            const double c2v = N2 ? __builtin_ldexp((double)S2 / (double)N2, E - 1 - 24) : 0.0;
-            c1[mb] = (uint16_t)double_to_half_bits(c1v);
+            const double c2v = N2 ? S2 / ((double)N2 * pow2_neg(2 * (E - 1))) : 0.0;
+            c1[mb] = (uint16_t)double_to_half_bits(proj);
             c2[mb] = (uint16_t)double_to_half_bits(c2v);
         }
-        __builtin_amdgcn_wave_barrier();             // the next block overwrites x and r
     }
 }
 
@@ -203,13 +211,13 @@ int goq_launch_quantize(hipStream_t st, int bw, int64_t out, int64_t in, const u
                         uint8_t *pattern, uint8_t *signs, uint16_t *c1, uint16_t *c2)
 {
     const int64_t nblocks = out * (in / GOQ_N);
-    int64_t grid = (nblocks + QW - 1) / QW;
-    if (grid > 256 * 16) grid = 256 * 16;            // 16 workgroups per CU, each wavefront walks its share
+    int64_t grid = (nblocks + QW * ROWS - 1) / (QW * ROWS);
+    if (grid > 256 * 32) grid = 256 * 32;            // every wavefront walks its share of the row groups
     if (bw == 3)
-        hipLaunchKernelGGL(quantize_kernel<3>, dim3((unsigned)grid), dim3(64 * QW), 0, st, (const uint32_t *)w, nblocks,
-                           (uint16_t *)codes, pattern, signs, c1, c2);
+        hipLaunchKernelGGL(quantize_kernel<3>, dim3((unsigned)grid), dim3(64 * QW), 0, st, (const uint4 *)w, nblocks,
+                           (uint2 *)codes, pattern, signs, c1, c2);
     else
-        hipLaunchKernelGGL(quantize_kernel<4>, dim3((unsigned)grid), dim3(64 * QW), 0, st, (const uint32_t *)w, nblocks,
-                           (uint16_t *)codes, pattern, signs, c1, c2);
+        hipLaunchKernelGGL(quantize_kernel<4>, dim3((unsigned)grid), dim3(64 * QW), 0, st, (const uint4 *)w, nblocks,
+                           (uint2 *)codes, pattern, signs, c1, c2);
     return goq_check_launch("goq_quantize");
 }
