@@ -130,8 +130,9 @@ __global__ __launch_bounds__(64 * QW) void quantize_kernel(const uint4 *__restri
         double s1 = 0.0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const double wa = half_bits_to_double(h[i] & 0x7fffu);
-            const bool neg = (h[i] & 0x8000u) != 0;
+            wv[i] = half_bits_to_double(h[i]);
+            const double wa = fabs(wv[i]);
+            const uint32_t neg = h[i] >> 15;                         // 1 for a negative weight
             int cnt = 0;
 #pragma unroll
             for (int k = 0; k <= E - 3; ++k) cnt += (wa <= 0.75 * pow2_neg(k) * sn) ? 1 : 0;
@@ -139,15 +140,15 @@ __global__ __launch_bounds__(64 * QW) void quantize_kernel(const uint4 *__restri
             const int cp = cnt + ((wa <= pow2_neg(E - 1) * sn) ? 1 : 0);
             // negative: exponent cn, or zero when no threshold is exceeded (cn = E);
             // positive: exponent cp, where cp = E - 1 is the code of zero already
-            const bool is_zero = zero_block || (neg ? cn == E : cp == E - 1);
             const int e = neg ? cn : cp;
-            const int code = is_zero ? E - 1 : ((neg ? E : 0) | e);
-            if (i < 4) code_lo |= (uint32_t)code << (8 * i);
-            else code_hi |= (uint32_t)code << (8 * (i - 4));
-            const double xa = is_zero ? 0.0 : pow2_neg(e);           // |b1_i|
-            x[i] = neg ? -xa : xa;
-            wv[i] = neg ? -wa : wa;
-            s1 += wa * xa;                                          // a weight and its state share the sign
+            const bool is_zero = zero_block || e == E - 1 + (int)neg;
+            const uint32_t code = is_zero ? (uint32_t)(E - 1) : ((neg << (BW - 1)) | (uint32_t)e);
+            if (i < 4) code_lo |= code << (8 * i);
+            else code_hi |= code << (8 * (i - 4));
+            // b1_i = (-1)^neg 2^-e assembled from sign and exponent field (low word zero)
+            const uint32_t xhi = is_zero ? 0u : (((uint32_t)(1023 - e) << 20) | (neg << 31));
+            x[i] = __hiloint2double((int)xhi, 0);
+            s1 += wa * fabs(x[i]);                                  // a weight and its state share the sign
             n1 += is_zero ? 0u : (1u << (2 * (E - 1 - e)));         // |b1_i|^2 in units of 4^-(E-1)
         }
         if (valid) codes[mb * 16 + m] = make_uint2(code_lo, code_hi);
