@@ -413,11 +413,11 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
 
 def bench_quantize(args, shapes, bw, name):
     """The GEO quantizer on the device (goq_quantize): a step quantizes every matrix of the block.
-    Not the headline metric: reported in weights/s.  It is bound by vector arithmetic (one
-    wavefront per macro-block; the sums of the method are carried out as exact 64-bit integer
-    sums, the residual, cross terms and scores in fp64), so the roofline is the fp64 vector peak
-    against the method's real-arithmetic operations per weight; its HBM traffic (2 B read + 1 B
-    codes + 0.25 B metadata + 4/128 B coefficients written per weight) is reported under config."""
+    Not the headline metric: reported in weights/s.  It is bound by vector-ALU issue (one lane per
+    micro-block, everything in registers, fp64 arithmetic with exact sums), so the roofline is the
+    fp64 vector peak against the method's real-arithmetic operations per weight; its HBM traffic
+    (2 B read + 1 B codes + 0.25 B metadata + 4/128 B coefficients written per weight) is reported
+    under config."""
     import torch
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")

@@ -19,9 +19,9 @@
 //   nearest     Q(v), v = w / s_norm (Sec. 3.2), is decided without the division: |v| lies above
 //               the midpoint 0.75 * 2^-k of the states 2^-k and 2^-(k+1) exactly when
 //               |w| > 0.75 * 2^-k * s_norm, and above the midpoint to zero, 2^-(emin+1), when
-//               |w| > 2^-(emin+1) * s_norm; the right-hand sides are exact in fp64 (s_norm has 11
-//               significant bits).  The thresholds fall with k, so the exponent of the nearest
-//               state is the NUMBER of thresholds |w| does not exceed; an exact tie goes to the
+//               |w| > 2^-(emin+1) * s_norm.  The thresholds fall with k, so the exponent of the
+//               nearest state is the NUMBER of thresholds |w| does not exceed, and that number is
+//               a difference of fp64 exponent fields (see the loop); an exact tie goes to the
 //               smaller magnitude.
 //   roundings   Only what the method defines as real arithmetic rounds: the projection
 //               coefficient <w,b1> / ||b1||^2 (one correctly rounded division of two exact
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(64 * QW) void quantize_kernel(const uint4 *__restri
         // nearest states.  Thresholds common to both signs: 0.75 2^-k s_norm, k = 0 .. E-3; then a
         // negative weight has the state 2^-(E-1) (midpoints 0.75 2^-(E-2) s_norm and, to zero,
         // 2^-E s_norm), a positive one ends at 2^-(E-2) (midpoint to zero 2^-(E-1) s_norm).
+        const int T075 = __double2hiint(0.75 * sn), Tsn = __double2hiint(sn);
         double wv[8], x[8];
         uint32_t code_lo = 0, code_hi = 0, n1 = 0;
         double s1 = 0.0;
@@ -133,14 +134,15 @@ __global__ __launch_bounds__(64 * QW) void quantize_kernel(const uint4 *__restri
             wv[i] = half_bits_to_double(h[i]);
             const double wa = fabs(wv[i]);
             const uint32_t neg = h[i] >> 15;                         // 1 for a negative weight
-            int cnt = 0;
-#pragma unroll
-            for (int k = 0; k <= E - 3; ++k) cnt += (wa <= 0.75 * pow2_neg(k) * sn) ? 1 : 0;
-            const int cn = cnt + ((wa <= 0.75 * pow2_neg(E - 2) * sn) ? 1 : 0) + ((wa <= pow2_neg(E) * sn) ? 1 : 0);
-            const int cp = cnt + ((wa <= pow2_neg(E - 1) * sn) ? 1 : 0);
-            // negative: exponent cn, or zero when no threshold is exceeded (cn = E);
-            // positive: exponent cp, where cp = E - 1 is the code of zero already
-            const int e = neg ? cn : cp;
+            // Number of thresholds |w| does not exceed.  |w| (11 significant bits) and 0.75 s_norm
+            // (13) are positive fp64 numbers whose low words are zero, so they order like their high
+            // words, and a factor 2^k is k units of the exponent field (bit 20 of the high word):
+            // |w| 2^k <= 0.75 s_norm  <=>  A + (k << 20) <= T.  That holds for k = 0 .. (T - A) >> 20
+            // when T >= A and for no k otherwise; a negative weight has E - 1 such thresholds, a
+            // positive one E - 2, and the midpoint to zero is one more comparison.
+            const int A = __double2hiint(wa);
+            const int nth = min(max(((T075 - A) >> 20) + 1, 0), E - 2 + (int)neg);
+            const int e = nth + ((A <= Tsn - ((E - 1 + (int)neg) << 20)) ? 1 : 0);
             const bool is_zero = zero_block || e == E - 1 + (int)neg;
             const uint32_t code = is_zero ? (uint32_t)(E - 1) : ((neg << (BW - 1)) | (uint32_t)e);
             if (i < 4) code_lo |= code << (8 * i);
