@@ -477,7 +477,7 @@ def bench_quantize(args, shapes, bw, name):
             O.quantize_geo(bw, w, threads=threads)
             reps += 1
             el = time.perf_counter() - t0
-            if el > 10.0 or reps >= 50:
+            if el > 10.0 or reps >= 5000:
                 break
         res["cpu_baseline"] = {"value": round(w.size * reps / el / 1e9, 5), "unit": "Gweights/s", "cores": threads,
                                "kind": "oracle", "sample": "%d pass(es) over the first 1024 rows of the first matrix (%d weights), %.1f s"
@@ -557,7 +557,7 @@ def bench_ref(args, shapes, bw, tokens, name):
             O.ref_coefficients(qs, w[:rows], x[:tk], lam=1e-4, threads=threads)
             reps += 1
             el = time.perf_counter() - t0
-            if el > 10.0 or reps >= 50:
+            if el > 10.0 or reps >= 5000:
                 break
         # weights/s at the benchmark's token count: the oracle's cost is linear in the tokens
         res["cpu_baseline"] = {"value": round(rows * w.shape[1] * reps / el / 1e9 * tk / tokens, 6), "unit": "Gweights/s",
@@ -589,7 +589,7 @@ def cpu_baseline_gemm(w0, shapes, bw, act_name, tokens):
             O.gemm_a8(canon[0], x, sx, threads=threads)
         reps += 1
         el = time.perf_counter() - t0
-        if el > 10.0 or reps >= 200:
+        if el > 10.0 or reps >= 20000:
             break
     return {"value": round(4.0 * slab * out * inn * reps / el / 1e12, 5), "unit": "TOP/s (issued)", "cores": threads,
             "kind": "oracle", "sample": "%d pass(es) over a %d-token slab of the first matrix (%dx%d), all outputs, %.1f s"
@@ -610,7 +610,7 @@ def cpu_baseline_gemv(host_w, shapes, bw, alg_bytes):
             O.gemm_a16(q, x, threads=threads)
         reps += 1
         el = time.perf_counter() - t0
-        if el > 10.0 or reps >= 20:
+        if el > 10.0 or reps >= 2000:
             break
     return {"value": round(alg_bytes * reps / el / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": "%d pass(es) of the full block (all %d GEMVs, all rows), %.1f s" % (reps, len(shapes), el)}
