@@ -210,8 +210,8 @@ int goq_mfma_probe(void *stream, int32_t *report);
 int goq_read_probe(void *stream, const void *buf, size_t bytes, uint32_t *sink);
 int goq_mfma_rate_probe(void *stream, int kind, int workgroups, int iters, float *sink, double *ops);
 
-/* Which of the two batch-1 kernels goq_gemv / goq_gemv_batch launch (process-wide, takes effect
- * with the next call; both kernels compute the same sums of Eq. 4 and both accept every shape):
+/* Which of the two batch-1 kernels goq_gemv / goq_gemv_batch launch when called from THIS thread
+ * (a per-thread setting, takes effect with the thread's next call; both kernels compute the same sums of Eq. 4 and both accept every shape):
  *   GOQ_GEMV_AUTO   (default) by size: launches of at most 512 tiles of 16 output rows (each
  *                   problem's rows rounded up to 16) and at most 24576 (tile, macro-block)
  *                   pairs -- 48 Mi weights -- go to the row-owner kernel, everything else streams;

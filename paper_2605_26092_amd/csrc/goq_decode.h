@@ -74,3 +74,31 @@ __device__ __forceinline__ void goq_decode_bytes(uint32_t w, uint32_t &lo, uint3
         }
     }
 }
+
+// Exchange table entry of variant v = pattern | signs << 2 (Theorem 1) for decoded BYTES:
+//   x, y : v_perm selectors, byte i of b2 = byte (i xor s) of b1 (s = pattern + 1)
+//   z, w : FLIP in the bytes whose sign flips: b2_i = -eta b1_j for the lower index of a pair,
+//          +eta b1_i for the upper one.  FLIP = 0x80 flips the sign bit of a float byte (fp16 high
+//          byte, E5M2); 0xFF marks the byte for a two's complement negation (int8).
+// Sign bit p of the descriptor belongs to the p-th pair in ascending lower index (the printed order
+// of the pair sets P_s).
+template <uint32_t FLIP>
+__device__ __forceinline__ uint4 goq_exchange_entry(int v)
+{
+    const int s = (v & 3) + 1;
+    const int sg = v >> 2;
+    uint32_t mlo = 0, mhi = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int j = i ^ s;
+        const int l = i < j ? i : j;
+        const int p = (s == 1) ? (l >> 1) : (s == 4) ? l : ((l & 1) | ((l >> 2) << 1));
+        const int eta_neg = (sg >> p) & 1;
+        const int lower = i < j;
+        const uint32_t flip = (uint32_t)(eta_neg ^ lower) * FLIP;
+        if (i < 4) mlo |= flip << (8 * i);
+        else mhi |= flip << (8 * (i - 4));
+    }
+    const uint32_t srep = (uint32_t)s * 0x01010101u;
+    return make_uint4(0x03020100u ^ srep, 0x07060504u ^ srep, mlo, mhi);
+}

@@ -75,31 +75,6 @@ struct GemmBatch {
     GemmArgs p[GOQ_MAX_BATCH];
 };
 
-// Exchange table entry of variant v = pattern | signs << 2 (Theorem 1):
-//   x, y : v_perm selectors, byte i of b2 = byte (i xor s) of b1
-//   z, w : per-byte masks of the elements whose sign flips (0x80 for fp16 high bytes, 0xFF for
-//          int8): b2_i = -eta b1_j for the lower index of a pair, +eta b1_i for the upper one.
-template <int ACT>
-__device__ __forceinline__ uint4 exchange_entry(int v)
-{
-    const int s = (v & 3) + 1;
-    const int sg = v >> 2;
-    uint32_t mlo = 0, mhi = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int j = i ^ s;
-        const int l = i < j ? i : j;
-        const int p = (s == 1) ? (l >> 1) : (s == 4) ? l : ((l & 1) | ((l >> 2) << 1));
-        const int eta_neg = (sg >> p) & 1;
-        const int lower = i < j;
-        const uint32_t flip = (uint32_t)(eta_neg ^ lower) * (ACT == 0 ? 0x80u : 0xFFu);
-        if (i < 4) mlo |= flip << (8 * i);
-        else mhi |= flip << (8 * (i - 4));
-    }
-    const uint32_t srep = (uint32_t)s * 0x01010101u;
-    return make_uint4(0x03020100u ^ srep, 0x07060504u ^ srep, mlo, mhi);
-}
-
 // LDS address of the exchange table entry of a micro-block: vt + 16 * (pattern | signs << 2)
 template <int BW>
 __device__ __forceinline__ uint32_t exchange_address(uint32_t w, const uint4 &meta, int m, uint32_t vt)
@@ -197,7 +172,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
     const int m0 = mt * TM;
     const int n0 = nt * TN + wave * WN;
 
-    if (tid < 64) *reinterpret_cast<uint4 *>(xtab + tid * 16) = exchange_entry<WACT>(tid);
+    if (tid < 64) *reinterpret_cast<uint4 *>(xtab + tid * 16) = goq_exchange_entry<(WACT == 0 ? 0x80u : 0xFFu)>(tid);
     const uint32_t vt = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)xtab;
 
     f32x16 Yacc[MS];

@@ -165,31 +165,6 @@ struct Pieces {
     Region *scratch;
 };
 
-// Exchange table entry of variant v = pattern | signs << 2 (Theorem 1) for decoded BYTES:
-//   x, y : v_perm selectors, byte i of b2 = byte (i xor s) of b1
-//   z, w : 0x80 in the bytes whose sign flips: b2_i = -eta b1_j for the lower index of a
-//          pair, +eta b1_i for the upper one.
-__device__ __forceinline__ uint4 exchange_entry(int v)
-{
-    const int s = (v & 3) + 1;
-    const int sg = v >> 2;
-    uint32_t mlo = 0, mhi = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int j = i ^ s;
-        const int l = i < j ? i : j;
-        // rank of the pair in ascending-lower-index order (the printed order of P_s)
-        const int p = (s == 1) ? (l >> 1) : (s == 4) ? l : ((l & 1) | ((l >> 2) << 1));
-        const int eta_neg = (sg >> p) & 1;
-        const int lower = i < j;
-        const uint32_t flip = (uint32_t)(eta_neg ^ lower) * 0x80u;
-        if (i < 4) mlo |= flip << (8 * i);
-        else mhi |= flip << (8 * (i - 4));
-    }
-    const uint32_t srep = (uint32_t)s * 0x01010101u;
-    return make_uint4(0x03020100u ^ srep, 0x07060504u ^ srep, mlo, mhi);
-}
-
 // What one lane holds of one unit: for j = 0..3 the quad (chunk q, row 16 j + c); for bw = 4
 // also the metadata dword of chunk q of that row.
 template <int BW>
@@ -661,7 +636,7 @@ __device__ __forceinline__ void stream_piece(const Problems<TABLE> &pb, const Pi
     Stream S = stream_of<KEEP>(pb, cur.pi);
     load_unit<BW>(S.packed, S.gn, min(cur.rg * WAVES + wave, S.rbn - 1), cur.g, lane, bufA);
 
-    for (int t = tid; t < 64 * VC; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t / VC);
+    for (int t = tid; t < 64 * VC; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = goq_exchange_entry<0x80u>(t / VC);
     if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
 
     // A operand of this lane: row = lane % 16, k-group q = lane / 16.  Digit d sits in row
@@ -870,7 +845,7 @@ void gemv_rows_kernel(GemvArgs a)
     Slice cur[RS], nxt[RS];
     request(0, cur);
 
-    for (int t = tid; t < 64 * VC; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = exchange_entry(t / VC);
+    for (int t = tid; t < 64 * VC; t += NT) *reinterpret_cast<uint4 *>(vtab + t * 16) = goq_exchange_entry<0x80u>(t / VC);
     if (tid < XZ / 4) reinterpret_cast<uint32_t *>(xtab)[tid] = 0u;
 
     // A operand of this lane, as in the kernel above
@@ -1017,7 +992,9 @@ Region *region_of_stream(hipStream_t st, int *rc)
     return D.base + free_slot;
 }
 
-std::atomic<int> g_kernel{GOQ_GEMV_AUTO};
+// selection of goq_gemv_select: a property of the calling thread, so that one caller's experiment
+// or test cannot change what another thread of the process launches
+thread_local int g_kernel = GOQ_GEMV_AUTO;
 
 void fill_problem(GemvProblem &P, const goq_gemv_desc &d)
 {
@@ -1037,7 +1014,7 @@ void fill_problem(GemvProblem &P, const goq_gemv_desc &d)
 
 }  // namespace
 
-void goq_gemv_set_kernel(int kernel) { g_kernel.store(kernel, std::memory_order_relaxed); }
+void goq_gemv_set_kernel(int kernel) { g_kernel = kernel; }
 
 size_t goq_gemv_workspace_size() { return sizeof(Region); }
 
@@ -1060,7 +1037,7 @@ int goq_gemv_plan_launch(int n, const goq_gemv_desc *descs, int *kernel, int *wo
         if (units > 0x3fffffff || blocks > 0x3fffffff)
             return goq_set_error(GOQ_ESHAPE, "goq_gemv: too much work for one launch");
     }
-    const int which = g_kernel.load(std::memory_order_relaxed);
+    const int which = g_kernel;
     const bool rows = which == GOQ_GEMV_ROWS ||
                       (which == GOQ_GEMV_AUTO && blocks <= ROWS_MAX_TILES && slices <= ROWS_MAX_SLICES);
     *kernel = rows ? GOQ_GEMV_ROWS : GOQ_GEMV_STREAM;
