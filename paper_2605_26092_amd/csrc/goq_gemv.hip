@@ -7,8 +7,8 @@
 // was the limit.  Here the vector ALU only DECODES: a 3-bit code becomes, with one byte look-up
 // permute, the 8-bit float (E5M2) of its power of two -- E5M2 is exactly the high byte of the
 // fp16 value, and a power of two has no other nonzero byte -- and b2 is rebuilt from b1 by the
-// Theorem 1 exchange as one more byte permute plus a sign XOR (the "exchange multiplexer and
-// sign XOR gate" of Sec. 3.3, driven by the 6 stored metadata bits).  The multiply-accumulates
+// Theorem 1 exchange as one more byte permute plus a sign XOR (what Sec. 3.3 builds from a
+// four-way exchange multiplexer and an XOR gate per lane, driven by the 6 stored metadata bits).  The multiply-accumulates
 // run on v_mfma_f32_16x16x128_f8f6f4 as a 16-row x 128-deep product per instruction:
 //
 //   B operand (weights): lane l = (column c = l % 16, k-group q = l / 16) supplies the 32 decoded
@@ -45,7 +45,6 @@
 // of a model -- as ONE unit sequence, so that start-up and tail are paid once per stream).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
-#include <atomic>
 #include <mutex>
 #include <string.h>
 #include <stddef.h>
