@@ -329,6 +329,10 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, 
         elif act == goq.A8:
             x, sx = goq_inputs.activations_a8(tokens, inn, config_id=4, tensor_id=200 + idx)
             sxs.append(torch.from_numpy(sx).to(dev))
+        elif act == goq.A6:
+            x, sx = goq_inputs.activations_int(tokens, inn, 6, config_id=4, tensor_id=200 + idx)
+            x = goq_inputs.pack_int6(x)
+            sxs.append(torch.from_numpy(sx).to(dev))
         else:
             x, sx = goq_inputs.activations_int(tokens, inn, 4, config_id=4, tensor_id=200 + idx)
             x = goq_inputs.pack_int4(x)
@@ -376,7 +380,7 @@ def bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=10, warmup=2, 
                 traffic, traffic_source = t["hbm_bytes_per_launch"], t.get("source")
         except (OSError, KeyError, ValueError):
             pass
-    return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, {goq.A16: "A16", goq.A8: "A8", goq.A4: "A4"}[act]),
+    return {"workload": "same block as GEMMs, %d tokens, W%d/%s" % (tokens, bw, {goq.A16: "A16", goq.A8: "A8", goq.A4: "A4", goq.A6: "A6"}[act]),
             "ms_per_block": round(ms, 4), "issued_TOPS": round(tops, 1),
             "dense_equiv_TOPS": round(tops if folded else tops / 2, 1),
             "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": peak, "unit": "TFLOP/s" if f16_path else "TOP/s",
@@ -391,7 +395,7 @@ def bench_gemm_only(args, shapes, bw, act_name, tokens, name, folded=False):
     import paper_2605_26092_amd as goq
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    act = {"A16": goq.A16, "A8": goq.A8, "A4": goq.A4}[act_name]
+    act = {"A16": goq.A16, "A8": goq.A8, "A4": goq.A4, "A6": goq.A6}[act_name]
     packed, host_w = quantize_block_on_device(goq, torch, shapes, bw, 3, dev)
     g = bench_gemm_block(args, shapes, bw, act, packed, tokens, steps=max(3, min(args.steps, 20)), warmup=2,
                          folded=folded)
@@ -580,7 +584,7 @@ def cpu_baseline_gemm(w0, shapes, bw, act_name, tokens):
     elif act_name == "A8":
         x, sx = goq_inputs.activations_a8(slab, inn, config_id=4, tensor_id=200)
     else:
-        x, sx = goq_inputs.activations_int(slab, inn, 4, config_id=4, tensor_id=200)
+        x, sx = goq_inputs.activations_int(slab, inn, 6 if act_name == "A6" else 4, config_id=4, tensor_id=200)
     reps, t0 = 0, time.perf_counter()
     while True:
         if act_name == "A16":
@@ -625,7 +629,7 @@ def main():
                     help="GEMV workloads: milliseconds of untimed launches before the warm-up that let the GPU clocks settle")
     ap.add_argument("--stream-blocks", type=int, default=0,
                     help="GEMV workloads: blocks per goq_gemv_stream launch (0 = by workload: 32 for the 7B block)")
-    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3", "c3_gemm_folded", "c2_gemv_w4"])
+    ap.add_argument("--workload", default="c2_gemv", choices=["c2_gemv", "c1_gemv", "c5_gemv", "c3_gemm_w3", "c3_gemm_w4", "c4_gemm_a8", "c4_gemm_a4", "c4_gemm_a6", "c4_gemm_w4a8", "c5_gemm", "q_geo_w3", "q_geo_w4", "ref_w3", "c3_gemm_folded", "c2_gemv_w4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run a 256 MiB-in / 256 MiB-out elementwise kernel (reference for counter runs)")
@@ -661,6 +665,8 @@ def main():
         res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 3, "A8", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W3/A8")
     elif args.workload == "c4_gemm_a4":
         res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 3, "A4", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W3/A4")
+    elif args.workload == "c4_gemm_a6":
+        res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 3, "A6", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W3/A6 (packed int6)")
     elif args.workload == "c4_gemm_w4a8":
         res = bench_gemm_only(args, goq_inputs.VIT_B_BLOCK, 4, "A8", 197 * 64, "vit-b block GEMMs, 197x64 tokens, W4/A8")
     else:

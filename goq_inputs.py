@@ -78,6 +78,19 @@ def pack_int4(xq):
     return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
 
 
+def pack_int6(xq):
+    """int8 values in [-32, 31], [tokens, in] -> packed int6 bytes [tokens, 3 in / 4]: element k in
+    bits 6 k .. 6 k + 5 of the row read as a little-endian bit string, two's complement (storage
+    format only, no arithmetic)."""
+    u = (xq.astype(np.int32) & 0x3F).astype(np.uint32)
+    w = u[:, 0::4] | (u[:, 1::4] << 6) | (u[:, 2::4] << 12) | (u[:, 3::4] << 18)      # 24 bits per four elements
+    out = np.empty((xq.shape[0], xq.shape[1] // 4, 3), dtype=np.uint8)
+    out[:, :, 0] = w & 0xFF
+    out[:, :, 1] = (w >> 8) & 0xFF
+    out[:, :, 2] = (w >> 16) & 0xFF
+    return out.reshape(xq.shape[0], -1)
+
+
 # W3 code histogram measured by quantising `weights()` with the GEO quantizer; codes follow the
 # canonical numbering (0:+1, 1:+.5, 2:+.25, 3:0, 4:-1, 5:-.5, 6:-.25, 7:-.125).
 _W3_HIST = np.array([0.0205, 0.1249, 0.2153, 0.2104, 0.0202, 0.1251, 0.1511, 0.1324])

@@ -145,10 +145,12 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
     static_assert(!FOLD || (ACT == 0 && !PART), "the folded product exists for fp16 activations only");
     constexpr int CH = (BW == 3) ? 4 : 5;
     // ACT: 0 fp16 x; 1 int8 x, int8 MFMA; 2 int8 x widened to fp16; 3 packed int4 x unpacked to
-    // int8, int8 MFMA; 4 packed int4 x widened to fp16.  2..4 stage x through registers.
-    constexpr bool F16 = (ACT == 0 || ACT == 2 || ACT == 4);       // fp16 MFMA
+    // int8, int8 MFMA; 4 packed int4 x widened to fp16; 5 packed int6 x unpacked to int8, int8
+    // MFMA; 6 packed int6 x widened to fp16.  2..6 stage x through registers.
+    constexpr bool F16 = (ACT == 0 || ACT == 2 || ACT == 4 || ACT == 6);   // fp16 MFMA
     constexpr bool REGSTAGE = (ACT >= 2);
-    constexpr bool X4 = (ACT >= 3);                                // two activations per byte
+    constexpr bool X4 = (ACT == 3 || ACT == 4);                    // two activations per byte
+    constexpr bool X6 = (ACT == 5 || ACT == 6);                    // four activations per three bytes
     constexpr int WACT = F16 ? 0 : 1;                  // how the weights are decoded
     constexpr int XB = F16 ? 2 : 1;                    // bytes per activation in LDS
     constexpr int ROWB = GOQ_N * XB;                   // LDS row stride (XOR-swizzled, not padded)
@@ -245,23 +247,37 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
     // widened on their way into LDS.  A thread moves NPS 16-byte pieces per slab; a piece holds
     // 16 int8 or 32 int4 activations and becomes OUTP 16-byte pieces of the LDS row.
     // int -> fp16 without a conversion instruction: 0x6400 | u is the fp16 number 1024 + u.
-    constexpr int SRCROW = X4 ? GOQ_N / 2 : GOQ_N;                 // bytes of a slab row in memory
-    constexpr int SPR = SRCROW / 16;                               // 16-byte source pieces per row
+    // (int6: a source piece is 24 bytes = 32 activations = two 16-byte LDS pieces of int8, fetched
+    // as three 8-byte loads)
+    constexpr int SRCROW = X4 ? GOQ_N / 2 : X6 ? GOQ_N * 3 / 4 : GOQ_N;   // bytes of a slab row in memory
+    constexpr int SRCP = X6 ? 24 : 16;                             // bytes of a source piece
+    constexpr int SPR = SRCROW / SRCP;                             // source pieces per row
     constexpr int NPS = (TM * SPR + 255) / 256;
+    constexpr int NQ = X6 ? 2 : 1;                                 // uint4 registers per source piece (int6: 6 of 8 words used)
     constexpr int OUTP = ROWB / SPR / 16;                          // LDS pieces per source piece
-    const int64_t xpitch = X4 ? a.in / 2 : a.in;                   // bytes of a token row in memory
+    const int64_t xpitch = X4 ? a.in / 2 : X6 ? a.in / 4 * 3 : a.in;   // bytes of a token row in memory
     uint32_t soff[NPS];
 #pragma unroll
     for (int i = 0; i < NPS; ++i) {
         const int S = i * 256 + tid;
         int m = m0 + S / SPR;
         m = m < a.tokens ? m : a.tokens - 1;
-        soff[i] = (uint32_t)(m - m0) * (uint32_t)xpitch + (S % SPR) * 16;
+        soff[i] = (uint32_t)(m - m0) * (uint32_t)xpitch + (S % SPR) * SRCP;
     }
-    auto fetch_x = [&](int g, uint4 (&r)[NPS]) {
+    auto fetch_x = [&](int g, uint4 (&r)[NPS * NQ]) {
         const unsigned char *base = reinterpret_cast<const unsigned char *>(a.X) + (int64_t)m0 * xpitch + (int64_t)g * SRCROW;
 #pragma unroll
-        for (int i = 0; i < NPS; ++i) r[i] = *reinterpret_cast<const uint4 *>(base + soff[i]);
+        for (int i = 0; i < NPS; ++i) {
+            if constexpr (X6) {
+                const uint2 a0 = *reinterpret_cast<const uint2 *>(base + soff[i]);
+                const uint2 a1 = *reinterpret_cast<const uint2 *>(base + soff[i] + 8);
+                const uint2 a2 = *reinterpret_cast<const uint2 *>(base + soff[i] + 16);
+                r[2 * i] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                r[2 * i + 1] = make_uint4(a2.x, a2.y, 0u, 0u);
+            } else {
+                r[i] = *reinterpret_cast<const uint4 *>(base + soff[i]);
+            }
+        }
     };
     // four int8 -> two registers of two fp16
     auto widen_i8 = [](uint32_t d, uint32_t &h0, uint32_t &h1) {
@@ -280,16 +296,35 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
         b0 = goq_perm(od, ev, 0x05010400u);                        // elements 0, 1, 2, 3
         b1 = goq_perm(od, ev, 0x07030602u);                        // elements 4, 5, 6, 7
     };
-    auto write_x = [&](int g, const uint4 (&r)[NPS]) {
+    // four int6 (24 bits, element i in bits 6 i .. 6 i + 5) -> one register of four int8
+    auto unpack_i6 = [](uint32_t v) {
+        const uint32_t b = (v & 0x3Fu) | ((v << 2) & 0x3F00u) | ((v << 4) & 0x3F0000u) | ((v << 6) & 0x3F000000u);
+        return ((((b ^ 0x20202020u) | 0x80808080u) - 0x20202020u) ^ 0x80808080u);   // per byte: 6 -> 8 bits, signed
+    };
+    auto write_x = [&](int g, const uint4 (&r)[NPS * NQ]) {
         unsigned char *buf = xsb[g % NBUF];
 #pragma unroll
         for (int i = 0; i < NPS; ++i) {
             const int S = i * 256 + tid;
             const int row = S / SPR, cs = S % SPR;
             if (NPS * 256 > TM * SPR && S >= TM * SPR) continue;
-            const uint32_t d[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-            uint32_t o[16];                                        // up to four LDS pieces
-            if constexpr (ACT == 2) {
+            uint32_t o[16];                                        // the source piece's LDS pieces
+            if constexpr (X6) {
+                // 6 dwords = 8 groups of 24 bits; group j starts at bit 24 j
+                const uint32_t w[6] = {r[i * 2].x, r[i * 2].y, r[i * 2].z, r[i * 2].w, r[i * 2 + 1].x, r[i * 2 + 1].y};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int dwi = (24 * j) >> 5, sh = (24 * j) & 31;
+                    const uint32_t v = sh == 0 ? w[dwi] : sh == 8 ? (w[dwi] >> 8) : __builtin_amdgcn_alignbit(w[dwi + 1], w[dwi], sh);
+                    const uint32_t b = unpack_i6(v);
+                    if constexpr (ACT == 5) o[j] = b;
+                    else widen_i8(b, o[2 * j], o[2 * j + 1]);
+                }
+            }
+            const uint32_t d[4] = {r[i * NQ].x, r[i * NQ].y, r[i * NQ].z, r[i * NQ].w};
+            if constexpr (X6) {
+                (void)d;
+            } else if constexpr (ACT == 2) {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) widen_i8(d[k], o[2 * k], o[2 * k + 1]);
             } else if constexpr (ACT == 3) {
@@ -356,7 +391,7 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
 
     // Prologue: slabs 0 and 1 are requested and waited for.
     Weights wd, wn;
-    uint4 xr[NPS];
+    uint4 xr[NPS * NQ];
     load_weights(0, wd);
     if constexpr (REGSTAGE) {
         fetch_x(0, xr);
@@ -567,5 +602,7 @@ int goq_launch_gemm(hipStream_t st, int bw, int act, int n, const goq_gemm_desc 
     if (bw == 4 && act == GOQ_A16) return launch<4, 0>(st, b, n);
     if (bw == 4 && act == GOQ_A8) return launch<4, 2>(st, b, n);
     if (bw == 3 && act == GOQ_A4) return launch<3, 3>(st, b, n);
-    return launch<4, 4>(st, b, n);
+    if (bw == 4 && act == GOQ_A4) return launch<4, 4>(st, b, n);
+    if (bw == 3 && act == GOQ_A6) return launch<3, 5>(st, b, n);
+    return launch<4, 6>(st, b, n);
 }
