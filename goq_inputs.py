@@ -91,6 +91,21 @@ def pack_int6(xq):
     return out.reshape(xq.shape[0], -1)
 
 
+def pack_int3(xq):
+    """int8 values in [-4, 3], [tokens, in] -> packed int3 bytes [tokens, 3 in / 8]: element k in
+    bits 3 k .. 3 k + 2 of the row read as a little-endian bit string, two's complement (storage
+    format only, no arithmetic)."""
+    u = (xq.astype(np.int32) & 0x7).astype(np.uint32)
+    w = np.zeros((xq.shape[0], xq.shape[1] // 8), dtype=np.uint32)
+    for i in range(8):
+        w |= u[:, i::8] << (3 * i)                                                # 24 bits per eight elements
+    out = np.empty((xq.shape[0], xq.shape[1] // 8, 3), dtype=np.uint8)
+    out[:, :, 0] = w & 0xFF
+    out[:, :, 1] = (w >> 8) & 0xFF
+    out[:, :, 2] = (w >> 16) & 0xFF
+    return out.reshape(xq.shape[0], -1)
+
+
 # W3 code histogram measured by quantising `weights()` with the GEO quantizer; codes follow the
 # canonical numbering (0:+1, 1:+.5, 2:+.25, 3:0, 4:-1, 5:-.5, 6:-.25, 7:-.125).
 _W3_HIST = np.array([0.0205, 0.1249, 0.2153, 0.2104, 0.0202, 0.1251, 0.1511, 0.1324])

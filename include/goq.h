@@ -55,9 +55,10 @@ enum {
 /* activation type (b_a-bit integer activations with scale s_x of Eq. 4): fp16 | int8 with a per-token
  * scale | int4, two per byte (element 2 i in the low nibble of byte i, two's complement), with a
  * per-token scale | int6, four per three bytes (element k in bits 6 k .. 6 k + 5 of the token's
- * row read as a little-endian bit string, two's complement), with a per-token scale.  Integer
- * activations of any other width up to 8 bits go in as int8 (up to 4 bits: as int4). */
-enum { GOQ_A16 = 0, GOQ_A8 = 1, GOQ_A4 = 2, GOQ_A6 = 3 };
+ * row read as a little-endian bit string, two's complement), with a per-token scale | int3, eight
+ * per three bytes (element k in bits 3 k .. 3 k + 2 of the same bit string).  Integer activations
+ * of any other width go in the next larger container. */
+enum { GOQ_A16 = 0, GOQ_A8 = 1, GOQ_A4 = 2, GOQ_A6 = 3, GOQ_A3 = 4 };
 enum { GOQ_F16 = 0, GOQ_F32 = 1 };  /* output type                                      */
 
 #define GOQ_MAX_BATCH 8             /* problems per goq_gemv_batch / goq_gemm_batch call */
@@ -119,6 +120,7 @@ int goq_unpack(void *stream, int bw, int64_t out, int64_t in, const void *packed
  *   act = GOQ_A8 : x is int8 [in], sx points to one fp32 scale (device).  Both bit widths.
  *   act = GOQ_A4 : x is packed int4 [in / 2 bytes], sx as for GOQ_A8.
  *   act = GOQ_A6 : x is packed int6 [3 in / 4 bytes], sx as for GOQ_A8.
+ *   act = GOQ_A3 : x is packed int3 [3 in / 8 bytes], sx as for GOQ_A8.
  *   y is [out] of ytype.  The PoT codes are decoded to 8-bit floats (a power of two is exact in
  *   E5M2) and b2 is rebuilt from b1 by a byte permute and a sign flip; the two slab dot products
  *   run on the 8-bit-float matrix instruction against x written as block fixed point (24 bits
@@ -242,6 +244,7 @@ int goq_gemv_plan(int bw, int act, int n, const goq_gemv_desc *descs, int *kerne
  *   act = GOQ_A4 : X packed int4 [tokens][in / 2 bytes], sx fp32 [tokens]; unpacked to int8 (bw = 3)
  *                  or widened to fp16 (bw = 4) on the way into LDS, then as GOQ_A8.
  *   act = GOQ_A6 : X packed int6 [tokens][3 in / 4 bytes], otherwise as GOQ_A4.
+ *   act = GOQ_A3 : X packed int3 [tokens][3 in / 8 bytes], otherwise as GOQ_A4.
  *   partials (optional, integer activations only, else NULL): int32 [tokens][out][in/128][2] receives
  *   the exact slab partials P_1, P_2 (in units of 2^-(E-1)). */
 int goq_gemm(void *stream, int bw, int act, int64_t tokens, int64_t out, int64_t in,

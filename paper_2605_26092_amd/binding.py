@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgoq.so")
 _lib = None
 
-A16, A8, A4, A6 = 0, 1, 2, 3
+A16, A8, A4, A6, A3 = 0, 1, 2, 3, 4
 F16, F32 = 0, 1
 OK, EINVAL, ESHAPE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
 MAX_BATCH = 8

@@ -114,7 +114,7 @@ static int check_gemv_desc(const char *fn, int bw, int act, const goq_gemv_desc 
 {
     int rc = check_shape(fn, bw, d.out, d.in);
     if (rc) return rc;
-    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4 && act != GOQ_A6) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4 && act != GOQ_A6 && act != GOQ_A3) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
     if (d.ytype != GOQ_F16 && d.ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "%s: bad output type %d", fn, d.ytype);
     if (!d.packed || !d.x || !d.y) return goq_set_error(GOQ_EINVAL, "%s: NULL pointer", fn);
     if (act != GOQ_A16 && !d.sx) return goq_set_error(GOQ_EINVAL, "%s: integer activations need sx", fn);
@@ -171,7 +171,7 @@ int goq_gemv_plan(int bw, int act, int n, const goq_gemv_desc *descs, int *kerne
     if (!descs || !kernel || !workgroups) return goq_set_error(GOQ_EINVAL, "goq_gemv_plan: NULL pointer");
     if (n < 1 || n > GOQ_MAX_BATCH)
         return goq_set_error(GOQ_ESHAPE, "goq_gemv_plan: n = %d must be in 1..%d", n, GOQ_MAX_BATCH);
-    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4 && act != GOQ_A6) return goq_set_error(GOQ_EINVAL, "goq_gemv_plan: bad activation type %d", act);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4 && act != GOQ_A6 && act != GOQ_A3) return goq_set_error(GOQ_EINVAL, "goq_gemv_plan: bad activation type %d", act);
     for (int i = 0; i < n; ++i) {
         int rc = check_shape("goq_gemv_plan", bw, descs[i].out, descs[i].in);
         if (rc) return rc;
@@ -254,7 +254,7 @@ static int check_gemm_desc(const char *fn, int bw, int act, const goq_gemm_desc 
     int rc = check_shape(fn, bw, d.out, d.in);
     if (rc) return rc;
     if (d.tokens <= 0 || d.tokens > (1 << 24)) return goq_set_error(GOQ_ESHAPE, "%s: tokens = %lld out of range", fn, (long long)d.tokens);
-    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4 && act != GOQ_A6) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
+    if (act != GOQ_A16 && act != GOQ_A8 && act != GOQ_A4 && act != GOQ_A6 && act != GOQ_A3) return goq_set_error(GOQ_EINVAL, "%s: bad activation type %d", fn, act);
     if (d.ytype != GOQ_F16 && d.ytype != GOQ_F32) return goq_set_error(GOQ_EINVAL, "%s: bad output type %d", fn, d.ytype);
     if (!d.packed || !d.X || !d.Y) return goq_set_error(GOQ_EINVAL, "%s: NULL pointer", fn);
     if (act != GOQ_A16 && !d.sx) return goq_set_error(GOQ_EINVAL, "%s: integer activations need sx", fn);

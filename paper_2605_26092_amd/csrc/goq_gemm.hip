@@ -146,11 +146,14 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
     constexpr int CH = (BW == 3) ? 4 : 5;
     // ACT: 0 fp16 x; 1 int8 x, int8 MFMA; 2 int8 x widened to fp16; 3 packed int4 x unpacked to
     // int8, int8 MFMA; 4 packed int4 x widened to fp16; 5 packed int6 x unpacked to int8, int8
-    // MFMA; 6 packed int6 x widened to fp16.  2..6 stage x through registers.
-    constexpr bool F16 = (ACT == 0 || ACT == 2 || ACT == 4 || ACT == 6);   // fp16 MFMA
+    // MFMA; 6 packed int6 x widened to fp16; 7 packed int3 x unpacked to int8, int8 MFMA; 8 packed
+    // int3 x widened to fp16.  2..8 stage x through registers.
+    constexpr bool F16 = (ACT == 0 || ACT == 2 || ACT == 4 || ACT == 6 || ACT == 8);   // fp16 MFMA
     constexpr bool REGSTAGE = (ACT >= 2);
     constexpr bool X4 = (ACT == 3 || ACT == 4);                    // two activations per byte
     constexpr bool X6 = (ACT == 5 || ACT == 6);                    // four activations per three bytes
+    constexpr bool X3 = (ACT == 7 || ACT == 8);                    // eight activations per three bytes
+    constexpr bool I8OUT = (ACT == 3 || ACT == 5 || ACT == 7);     // staged as int8 (else widened to fp16)
     constexpr int WACT = F16 ? 0 : 1;                  // how the weights are decoded
     constexpr int XB = F16 ? 2 : 1;                    // bytes per activation in LDS
     constexpr int ROWB = GOQ_N * XB;                   // LDS row stride (XOR-swizzled, not padded)
@@ -247,15 +250,15 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
     // widened on their way into LDS.  A thread moves NPS 16-byte pieces per slab; a piece holds
     // 16 int8 or 32 int4 activations and becomes OUTP 16-byte pieces of the LDS row.
     // int -> fp16 without a conversion instruction: 0x6400 | u is the fp16 number 1024 + u.
-    // (int6: a source piece is 24 bytes = 32 activations = two 16-byte LDS pieces of int8, fetched
-    // as three 8-byte loads)
-    constexpr int SRCROW = X4 ? GOQ_N / 2 : X6 ? GOQ_N * 3 / 4 : GOQ_N;   // bytes of a slab row in memory
-    constexpr int SRCP = X6 ? 24 : 16;                             // bytes of a source piece
+    // (int6 / int3: a source piece is 24 / 12 bytes = 32 activations = two 16-byte LDS pieces of
+    // int8, fetched as three 8-byte / 4-byte loads)
+    constexpr int SRCROW = X4 ? GOQ_N / 2 : X6 ? GOQ_N * 3 / 4 : X3 ? GOQ_N * 3 / 8 : GOQ_N;   // bytes of a slab row in memory
+    constexpr int SRCP = X6 ? 24 : X3 ? 12 : 16;                   // bytes of a source piece
     constexpr int SPR = SRCROW / SRCP;                             // source pieces per row
     constexpr int NPS = (TM * SPR + 255) / 256;
     constexpr int NQ = X6 ? 2 : 1;                                 // uint4 registers per source piece (int6: 6 of 8 words used)
     constexpr int OUTP = ROWB / SPR / 16;                          // LDS pieces per source piece
-    const int64_t xpitch = X4 ? a.in / 2 : X6 ? a.in / 4 * 3 : a.in;   // bytes of a token row in memory
+    const int64_t xpitch = X4 ? a.in / 2 : X6 ? a.in / 4 * 3 : X3 ? a.in / 8 * 3 : a.in;   // bytes of a token row in memory
     uint32_t soff[NPS];
 #pragma unroll
     for (int i = 0; i < NPS; ++i) {
@@ -274,6 +277,9 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
                 const uint2 a2 = *reinterpret_cast<const uint2 *>(base + soff[i] + 16);
                 r[2 * i] = make_uint4(a0.x, a0.y, a1.x, a1.y);
                 r[2 * i + 1] = make_uint4(a2.x, a2.y, 0u, 0u);
+            } else if constexpr (X3) {
+                const uint32_t *p3 = reinterpret_cast<const uint32_t *>(base + soff[i]);
+                r[i] = make_uint4(p3[0], p3[1], p3[2], 0u);
             } else {
                 r[i] = *reinterpret_cast<const uint4 *>(base + soff[i]);
             }
@@ -301,6 +307,15 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
         const uint32_t b = (v & 0x3Fu) | ((v << 2) & 0x3F00u) | ((v << 4) & 0x3F0000u) | ((v << 6) & 0x3F000000u);
         return ((((b ^ 0x20202020u) | 0x80808080u) - 0x20202020u) ^ 0x80808080u);   // per byte: 6 -> 8 bits, signed
     };
+    // eight int3 (24 bits, element i in bits 3 i .. 3 i + 2) -> two registers of four int8
+    auto unpack_i3 = [](uint32_t v, uint32_t &b0, uint32_t &b1) {
+        auto spread = [](uint32_t t) {
+            const uint32_t b = (t & 0x7u) | ((t << 5) & 0x700u) | ((t << 10) & 0x70000u) | ((t << 15) & 0x7000000u);
+            return ((((b ^ 0x04040404u) | 0x80808080u) - 0x04040404u) ^ 0x80808080u);   // per byte: 3 -> 8 bits, signed
+        };
+        b0 = spread(v);
+        b1 = spread(v >> 12);
+    };
     auto write_x = [&](int g, const uint4 (&r)[NPS * NQ]) {
         unsigned char *buf = xsb[g % NBUF];
 #pragma unroll
@@ -317,12 +332,24 @@ __global__ __launch_bounds__(256, GOQ_GEMM_MINWAVES) void gemm_kernel(GemmBatch 
                     const int dwi = (24 * j) >> 5, sh = (24 * j) & 31;
                     const uint32_t v = sh == 0 ? w[dwi] : sh == 8 ? (w[dwi] >> 8) : __builtin_amdgcn_alignbit(w[dwi + 1], w[dwi], sh);
                     const uint32_t b = unpack_i6(v);
-                    if constexpr (ACT == 5) o[j] = b;
+                    if constexpr (I8OUT) o[j] = b;
                     else widen_i8(b, o[2 * j], o[2 * j + 1]);
+                }
+            } else if constexpr (X3) {
+                // 3 dwords = 4 groups of 24 bits = 32 activations
+                const uint32_t w[3] = {r[i].x, r[i].y, r[i].z};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int dwi = (24 * j) >> 5, sh = (24 * j) & 31;
+                    const uint32_t v = sh == 0 ? w[dwi] : sh == 8 ? (w[dwi] >> 8) : __builtin_amdgcn_alignbit(w[dwi + 1], w[dwi], sh);
+                    uint32_t b0, b1;
+                    unpack_i3(v, b0, b1);
+                    if constexpr (I8OUT) { o[2 * j] = b0; o[2 * j + 1] = b1; }
+                    else { widen_i8(b0, o[4 * j], o[4 * j + 1]); widen_i8(b1, o[4 * j + 2], o[4 * j + 3]); }
                 }
             }
             const uint32_t d[4] = {r[i * NQ].x, r[i * NQ].y, r[i * NQ].z, r[i * NQ].w};
-            if constexpr (X6) {
+            if constexpr (X6 || X3) {
                 (void)d;
             } else if constexpr (ACT == 2) {
 #pragma unroll
@@ -604,5 +631,7 @@ int goq_launch_gemm(hipStream_t st, int bw, int act, int n, const goq_gemm_desc 
     if (bw == 3 && act == GOQ_A4) return launch<3, 3>(st, b, n);
     if (bw == 4 && act == GOQ_A4) return launch<4, 4>(st, b, n);
     if (bw == 3 && act == GOQ_A6) return launch<3, 5>(st, b, n);
-    return launch<4, 6>(st, b, n);
+    if (bw == 4 && act == GOQ_A6) return launch<4, 6>(st, b, n);
+    if (bw == 3 && act == GOQ_A3) return launch<3, 7>(st, b, n);
+    return launch<4, 8>(st, b, n);
 }

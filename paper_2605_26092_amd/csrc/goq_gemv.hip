@@ -221,8 +221,8 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ packed, i
 // count as 1).
 // The 8 activations of run r as four registers of two fp16 each, from the run's raw words:
 // raw[0..3] (fp16), raw[0..1] (int8), raw[0] (packed int4: element i in nibble i) or the low 48
-// bits of raw[1]:raw[0] (packed int6: element i in bits 6 i .. 6 i + 5).  Integer activations are
-// exact in fp16.
+// bits of raw[1]:raw[0] (packed int6: element i in bits 6 i .. 6 i + 5) or the low 24 bits of raw[0]
+// (packed int3: element i in bits 3 i .. 3 i + 2).  Integer activations are exact in fp16.
 template <int ACT>
 __device__ __forceinline__ void run_as_half(const uint32_t (&raw)[4], uint32_t (&v)[4])
 {
@@ -245,6 +245,15 @@ __device__ __forceinline__ void run_as_half(const uint32_t (&raw)[4], uint32_t (
             const goq_half2 hv = {(_Float16)e0, (_Float16)e1};
             v[d] = __builtin_bit_cast(uint32_t, hv);
         }
+    } else if constexpr (ACT == 4) {
+        const uint32_t q = raw[0];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int e0 = (int)(q << (29 - 6 * d)) >> 29;         // sign-extended field 2 d
+            const int e1 = (int)(q << (26 - 6 * d)) >> 29;         // field 2 d + 1
+            const goq_half2 hv = {(_Float16)e0, (_Float16)e1};
+            v[d] = __builtin_bit_cast(uint32_t, hv);
+        }
     } else {
         // fields 0..4 lie in raw[0], field 5 straddles the two words, 6 and 7 lie in raw[1]
         const uint32_t lo = raw[0], hi = (raw[0] >> 30) | (raw[1] << 2);     // hi: fields 5, 6, 7 from bit 0
@@ -261,7 +270,7 @@ __device__ __forceinline__ void run_as_half(const uint32_t (&raw)[4], uint32_t (
 
 // bytes of one macro-block's activations in memory
 template <int ACT>
-constexpr int unit_x_bytes() { return ACT == 0 ? 256 : ACT == 1 ? 128 : ACT == 2 ? 64 : 96; }
+constexpr int unit_x_bytes() { return ACT == 0 ? 256 : ACT == 1 ? 128 : ACT == 2 ? 64 : ACT == 3 ? 96 : 48; }
 
 // run r of macro-block g of x in global memory
 template <int ACT>
@@ -276,6 +285,13 @@ __device__ __forceinline__ void load_run(const void *x, int g, int r, uint32_t (
         raw[1] = ((gptr)x)[(int64_t)g * 32 + 2 * r + 1];
     } else if constexpr (ACT == 2) {
         raw[0] = ((gptr)x)[(int64_t)g * 16 + r];
+    } else if constexpr (ACT == 4) {
+        // the run's 3 bytes start at byte 3 r of the macro-block's 48; they reach into the next
+        // dword only when they start at byte 2 or 3 of theirs (never for the last run)
+        const gptr p = (gptr)x + ((int64_t)g * 12 + ((3 * r) >> 2));
+        const uint32_t sh = (uint32_t)((3 * r) & 3) * 8u;
+        const uint32_t d0 = p[0], d1 = sh > 8u ? p[1] : 0u;
+        raw[0] = sh ? __builtin_amdgcn_alignbit(d1, d0, sh) : d0;
     } else {
         // the run's 6 bytes start at byte 6 r of the macro-block's 96: in the two dwords from dword
         // 3 r / 2, at byte offset 0 (r even) or 2 (r odd)
@@ -1094,6 +1110,8 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
         if (bw == 4 && act == GOQ_A4) return launch_rows<4, 2>(st, a, nb);
         if (bw == 3 && act == GOQ_A6) return launch_rows<3, 3>(st, a, nb);
         if (bw == 4 && act == GOQ_A6) return launch_rows<4, 3>(st, a, nb);
+        if (bw == 3 && act == GOQ_A3) return launch_rows<3, 4>(st, a, nb);
+        if (bw == 4 && act == GOQ_A3) return launch_rows<4, 4>(st, a, nb);
         return launch_rows<4, 0>(st, a, nb);
     }
     a.scratch = reinterpret_cast<Region *>(workspace);
@@ -1112,6 +1130,8 @@ int goq_launch_gemv(hipStream_t st, int bw, int act, int n, const goq_gemv_desc 
     if (bw == 4 && act == GOQ_A4) return launch<4, 2>(st, a, nwg);
     if (bw == 3 && act == GOQ_A6) return launch<3, 3>(st, a, nwg);
     if (bw == 4 && act == GOQ_A6) return launch<4, 3>(st, a, nwg);
+    if (bw == 3 && act == GOQ_A3) return launch<3, 4>(st, a, nwg);
+    if (bw == 4 && act == GOQ_A3) return launch<4, 4>(st, a, nwg);
     return launch<4, 0>(st, a, nwg);
 }
 
@@ -1163,5 +1183,7 @@ int goq_launch_gemv_stream(hipStream_t st, const void *table_host, const void *t
     if (bw == 4 && act == GOQ_A4) return launch_stream<4, 2>(st, dev, ws, nwg);
     if (bw == 3 && act == GOQ_A6) return launch_stream<3, 3>(st, dev, ws, nwg);
     if (bw == 4 && act == GOQ_A6) return launch_stream<4, 3>(st, dev, ws, nwg);
+    if (bw == 3 && act == GOQ_A3) return launch_stream<3, 4>(st, dev, ws, nwg);
+    if (bw == 4 && act == GOQ_A3) return launch_stream<4, 4>(st, dev, ws, nwg);
     return launch_stream<4, 0>(st, dev, ws, nwg);
 }

@@ -53,7 +53,8 @@ def test_host_side_argument_errors(goq):
     assert L.goq_gemv(None, 3, 0, 64, 128, fake, fake, None, fake, 9) == b.EINVAL
     assert L.goq_gemv(None, 3, 1, 64, 128, fake, fake, None, fake, 1) == b.EINVAL      # A8 needs sx
     assert L.goq_gemv(None, 4, 2, 64, 128, fake, fake, None, fake, 1) == b.EINVAL      # A4 needs sx
-    assert L.goq_gemm(None, 3, 4, 4, 64, 128, fake, fake, fake, fake, 1, None) == b.EINVAL   # no such activation type
+    assert L.goq_gemm(None, 3, 5, 4, 64, 128, fake, fake, fake, fake, 1, None) == b.EINVAL   # no such activation type
+    assert L.goq_gemv(None, 3, 4, 64, 128, fake, fake, None, fake, 1) == b.EINVAL      # A3 needs sx
     assert L.goq_gemv(None, 3, 3, 64, 128, fake, fake, None, fake, 1) == b.EINVAL      # A6 needs sx
     assert L.goq_gemv(None, 3, 0, 64, 128, fake, fake, fake, fake, 1) == b.EINVAL      # A16 forbids sx
     assert L.goq_gemm_batch(None, 3, 0, 0, None) == b.EINVAL
