@@ -79,9 +79,6 @@ constexpr int XZ = 256;                  // zero bytes in front of the digit tab
 #ifndef GOQ_CB
 #define GOQ_CB 16
 #endif
-#ifndef GOQ_SCHED_GROUPS
-#define GOQ_SCHED_GROUPS 1
-#endif
 #ifndef GOQ_VCOPIES
 #define GOQ_VCOPIES 16
 #endif
@@ -267,10 +264,6 @@ __device__ __forceinline__ void run_as_half(const uint32_t (&raw)[4], uint32_t (
         }
     }
 }
-
-// bytes of one macro-block's activations in memory
-template <int ACT>
-constexpr int unit_x_bytes() { return ACT == 0 ? 256 : ACT == 1 ? 128 : ACT == 2 ? 64 : ACT == 3 ? 96 : 48; }
 
 // run r of macro-block g of x in global memory
 template <int ACT>
@@ -471,11 +464,9 @@ __device__ __forceinline__ void slice_products(const uint4 &quad, uint32_t md, u
         uint32_t eo[LA];
 #pragma unroll
         for (int k = 0; k < LA; ++k) eo[k] = address(k);
-#if GOQ_SCHED_GROUPS
 #pragma unroll
         for (int k = 0; k < LA; ++k) __builtin_amdgcn_sched_group_barrier(0x002, BW == 3 ? 2 : 3, 0);   // VALU
         __builtin_amdgcn_sched_group_barrier(0x100, LA, 0);                                            // DS read
-#endif
 #pragma unroll
         for (int k = 0; k < LA; ++k) fetch(k, eo[k]);
     }
