@@ -21,7 +21,8 @@ namespace {
 
 constexpr int RT = 256;                  // threads per workgroup (both kernels)
 constexpr int TT = 16;                   // tokens per LDS tile of the Gram kernel
-constexpr int OB = 32;                   // output channels per workgroup of the solve kernel
+constexpr int OPT = 2;                   // output channels per thread of the solve kernel
+constexpr int OB = 32 * OPT;             // output channels per workgroup of the solve kernel
 
 // ---- kernel 1: S_g = X_q^T X_q, one workgroup per macro-block, thread (ti, tj) owns the 8 x 8
 // block of rows 8 ti .., columns 8 tj ..
@@ -71,9 +72,11 @@ __global__ __launch_bounds__(RT) void gram_kernel(const uint16_t *__restrict__ X
 }
 
 // ---- kernel 2: per (g, block of OB output channels).  Thread (oo = tid % 32, ic = tid / 32) forms
-// rows 16 ic .. 16 ic + 15 of u1 = S_g b1 and u2 = S_g b2 of output channel oo (S_g is symmetric, so
-// column j of S_g is read as the contiguous row j), then its share of the five dot products; the
-// eight shares of an output channel are added in order and the 2 x 2 system is solved.
+// rows 16 ic .. 16 ic + 15 of u1 = S_g b1 and u2 = S_g b2 of the output channels oo, oo + 32, ..
+// (S_g is symmetric, so column j of S_g is read as the contiguous row j, and one read serves all of
+// a thread's channels), then its share of the five dot products; the eight shares of an output
+// channel are added in order and the 2 x 2 system is solved.  b1, b2 and w are staged as fp16,
+// which holds them exactly.
 template <int BW>
 __global__ __launch_bounds__(RT) void ref_solve_kernel(const uint16_t *__restrict__ w, const uint8_t *__restrict__ codes,
                                                        const uint8_t *__restrict__ pattern, const uint8_t *__restrict__ signs,
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(RT) void ref_solve_kernel(const uint16_t *__restric
                                                        double *__restrict__ craw, uint16_t *__restrict__ c1,
                                                        uint16_t *__restrict__ c2)
 {
-    __shared__ float vb1[OB][GOQ_N + 1], vb2[OB][GOQ_N + 1], vw[OB][GOQ_N + 1];
+    __shared__ _Float16 vb1[OB][GOQ_N + 2], vb2[OB][GOQ_N + 2], vw[OB][GOQ_N + 2];
     __shared__ double red[8][OB][5];
     const int tid = threadIdx.x;
     const int g = blockIdx.x;
@@ -115,46 +118,58 @@ __global__ __launch_bounds__(RT) void ref_solve_kernel(const uint16_t *__restric
             }
         }
 #pragma unroll
-        for (int i = 0; i < GOQ_G; ++i) { vb1[oo][m * GOQ_G + i] = x[i]; vb2[oo][m * GOQ_G + i] = y[i]; }
+        for (int i = 0; i < GOQ_G; ++i) { vb1[oo][m * GOQ_G + i] = (_Float16)x[i]; vb2[oo][m * GOQ_G + i] = (_Float16)y[i]; }
     }
     for (int it = tid; it < OB * GOQ_N; it += RT) {
         const int oo = it >> 7, k = it & 127;
         const int64_t o = min(o0 + oo, out - 1);
-        vw[oo][k] = (float)half_bits_to_double(w[o * in + (int64_t)g * GOQ_N + k]);
+        vw[oo][k] = __builtin_bit_cast(_Float16, w[o * in + (int64_t)g * GOQ_N + k]);
     }
     __syncthreads();
 
-    const int oo = tid & 31, ic = tid >> 5;
+    const int o32 = tid & 31, ic = tid >> 5;
     const double *Sg = S + (int64_t)g * GOQ_N * GOQ_N;
-    double u1[16], u2[16];
+    double u1[OPT][16], u2[OPT][16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { u1[r] = 0.0; u2[r] = 0.0; }
+    for (int c = 0; c < OPT; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { u1[c][r] = 0.0; u2[c][r] = 0.0; }
     for (int j = 0; j < GOQ_N; ++j) {
-        const double bj1 = (double)vb1[oo][j], bj2 = (double)vb2[oo][j];
+        double bj1[OPT], bj2[OPT];
+#pragma unroll
+        for (int c = 0; c < OPT; ++c) { bj1[c] = (double)(float)vb1[o32 + 32 * c][j]; bj2[c] = (double)(float)vb2[o32 + 32 * c][j]; }
         const double *row = Sg + j * GOQ_N + 16 * ic;           // S[j][16 ic ..] = S[16 ic ..][j]
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
             const double2 sv = *reinterpret_cast<const double2 *>(row + r);
-            u1[r] = fma(sv.x, bj1, u1[r]);
-            u1[r + 1] = fma(sv.y, bj1, u1[r + 1]);
-            u2[r] = fma(sv.x, bj2, u2[r]);
-            u2[r + 1] = fma(sv.y, bj2, u2[r + 1]);
+#pragma unroll
+            for (int c = 0; c < OPT; ++c) {
+                u1[c][r] = fma(sv.x, bj1[c], u1[c][r]);
+                u1[c][r + 1] = fma(sv.y, bj1[c], u1[c][r + 1]);
+                u2[c][r] = fma(sv.x, bj2[c], u2[c][r]);
+                u2[c][r + 1] = fma(sv.y, bj2[c], u2[c][r + 1]);
+            }
         }
     }
-    double g11 = 0.0, g12 = 0.0, g22 = 0.0, r1 = 0.0, r2 = 0.0;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int i = 16 * ic + r;
-        const double b1i = (double)vb1[oo][i], b2i = (double)vb2[oo][i], wi = (double)vw[oo][i];
-        g11 = fma(b1i, u1[r], g11);
-        g12 = fma(b2i, u1[r], g12);
-        g22 = fma(b2i, u2[r], g22);
-        r1 = fma(wi, u1[r], r1);
-        r2 = fma(wi, u2[r], r2);
+    for (int c = 0; c < OPT; ++c) {
+        const int oo = o32 + 32 * c;
+        double g11 = 0.0, g12 = 0.0, g22 = 0.0, r1 = 0.0, r2 = 0.0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = 16 * ic + r;
+            const double b1i = (double)(float)vb1[oo][i], b2i = (double)(float)vb2[oo][i], wi = (double)(float)vw[oo][i];
+            g11 = fma(b1i, u1[c][r], g11);
+            g12 = fma(b2i, u1[c][r], g12);
+            g22 = fma(b2i, u2[c][r], g22);
+            r1 = fma(wi, u1[c][r], r1);
+            r2 = fma(wi, u2[c][r], r2);
+        }
+        red[ic][oo][0] = g11; red[ic][oo][1] = g12; red[ic][oo][2] = g22; red[ic][oo][3] = r1; red[ic][oo][4] = r2;
     }
-    red[ic][oo][0] = g11; red[ic][oo][1] = g12; red[ic][oo][2] = g22; red[ic][oo][3] = r1; red[ic][oo][4] = r2;
     __syncthreads();
-    if (ic == 0 && o0 + oo < out) {
+    for (int oo = tid; oo < OB; oo += RT) {
+        if (o0 + oo >= out) continue;
         double q[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
         for (int c = 0; c < 8; ++c)
 #pragma unroll
