@@ -259,3 +259,39 @@ def test_stream_of_thousands_of_tiny_problems(oracle, bw, act_name):
         worst = max(worst, e)
         assert e <= TOL, (k, layers[pick[k]], e)
     print("tiny-problem stream: worst relative error %.3g" % worst, flush=True)
+
+
+def test_stream_with_the_maximum_number_of_problems(oracle):
+    """GOQ_MAX_STREAM = 65536 problems in one table (one more is refused on the host): the same
+    70 x 256 layer and activations 65536 times, each problem writing its own slice of one output
+    buffer; every slice must equal the first bit for bit and the oracle within tolerance."""
+    import paper_2605_26092_amd as goq
+    from paper_2605_26092_amd import binding
+    torch = gu.torch_cuda()
+    out, inn, n = 70, 256, 65536
+    q = oracle.quantize_geo(3, goq_inputs.weights(out, inn, config_id=65, tensor_id=0), threads=8)
+    x = goq_inputs.activations_a16(1, inn, config_id=65, tensor_id=100, outlier_frac=0.01)
+    ref = oracle.gemm_a16(q, x, threads=8)[0]
+    packed, xd = gu.pack_layer(goq, q), gu.to_dev(x.reshape(-1))
+    pitch = 80                                                     # floats per slice: 16-byte aligned slices
+    ybuf = torch.full((n * pitch,), float("nan"), dtype=torch.float32, device="cuda")
+    arr = (binding._Desc * n)()
+    base = ybuf.data_ptr()
+    for i in range(n):
+        d = arr[i]
+        d.out, d.in_, d.packed, d.x, d.sx, d.y, d.ytype = out, inn, packed.data_ptr(), xd.data_ptr(), None, base + 4 * pitch * i, goq.F32
+    nbytes = ctypes.c_size_t(0)
+    L = goq.lib()
+    assert L.goq_gemv_stream_table_bytes(n + 1, ctypes.byref(nbytes)) == binding.ESHAPE
+    print("max-size stream: %d problems" % n, flush=True)
+    ws = _workspace(goq)
+    th, tbytes = goq.gemv_stream_table(3, goq.A16, arr)
+    td = _table_to_device(th, tbytes)
+    goq.gemv_stream(th, td, ws)
+    torch.cuda.synchronize()
+    y = ybuf.view(n, pitch)[:, :out]
+    assert not torch.isnan(y).any()
+    assert torch.equal(y, y[0:1].expand(n, out))
+    e1, _ = gu.a16_errors(y[0].cpu().numpy(), ref, None)
+    assert e1 <= TOL, e1
+    assert torch.isnan(ybuf.view(n, pitch)[:, out:]).all()         # nothing written past a slice's rows
